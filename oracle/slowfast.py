@@ -1,0 +1,231 @@
+"""SlowFast selection rule, stage controller and decode loop -- CPU oracle.
+
+TEST INFRASTRUCTURE: plain Python over small arrays, written from Section 3.3
+("SlowFast Sampling") and Algorithm 1 of the paper, in the paper's order and
+notation.  It imports nothing from the HIP library.
+
+Positions are absolute and 0-based; a span [s, e] is inclusive at both ends.
+The generated region is [gen_start, gen_end) and the prompt is never masked.
+
+Readings taken where the paper is silent or at odds with itself:
+
+* Candidates are masked positions only: a committed token is never revisited
+  (one-way "unmask" wording of the cautious-decoding and in-span bullets).
+* The [MASK] id is not a legal prediction (handled in the row phase).
+* e_cand of a step whose confidences all fail tau_min is reported as -1; the
+  controller then uses the leftmost masked position of the window.
+* A step's commit set and its e_cand come from the same, pre-commit state.
+* Ties: top-k ranks by (higher confidence, lower position); thresholds are
+  strict ">" (eq. 6, eq. 9, and the "0.22 < 0.23" example of Fig. 3).
+* The Convergence Principle at token level ("stable identity over recent
+  steps"): with conv_mode = 1 a position joins S_high only if its prediction
+  equals the previous step's prediction; conv_mode = 0 is Algorithm 1 as printed.
+* The history H_W is reset at the start of every exploratory stage, the
+  variance is the population variance, and the mean is floored.
+* When K_max is reached without stability, e_cycle is the last e_cand
+  (Algorithm 1's fallback branch).
+* The fast stage repeats until no mask is left in [s_cycle, e_cycle]; then
+  s_cycle <- e_cycle + 1.
+* Every decision on a confidence is taken on its binary32 value.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Callable, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+SLOW, FAST, IDLE = 0, 1, 2
+
+
+@dataclass
+class StageParams:
+    """What one denoising step needs to know about one sequence."""
+    stage: int
+    s_cycle: int
+    e_cycle: int          # used by the fast stage only
+    top_k: int            # k_slow or k_fast
+    tau_min_conf: float
+    tau_high_conf: float
+    conv_mode: int
+    gen_start: int
+    gen_end: int
+
+    def window(self) -> Tuple[int, int]:
+        """Inclusive span the step looks at: [s_cycle, end of sequence] in the
+        slow stage, [s_cycle, e_cycle] in the fast stage; empty when idle."""
+        if self.stage == SLOW:
+            return self.s_cycle, self.gen_end - 1
+        if self.stage == FAST:
+            return self.s_cycle, self.e_cycle
+        return 0, -1
+
+
+@dataclass
+class DecodeParams:
+    max_steps: int                 # N
+    k_max: int = 8
+    w_hist: int = 2
+    sigma2_stable: float = 1.0
+    tau_min_conf: float = 0.1
+    tau_high_conf: float = 0.85
+    k_slow: int = 1
+    k_fast: int = 1
+    conv_mode: int = 0
+
+
+def active_rows(sp: StageParams, mask: np.ndarray) -> np.ndarray:
+    """Positions whose prediction the step needs: masked and inside the window."""
+    lo, hi = sp.window()
+    act = np.zeros(mask.shape[0], dtype=np.uint8)
+    for i in range(max(lo, 0), min(hi, mask.shape[0] - 1) + 1):
+        if mask[i]:
+            act[i] = 1
+    return act
+
+
+def top_k(cands: Sequence[int], conf: np.ndarray, k: int) -> List[int]:
+    order = sorted(cands, key=lambda i: (-float(conf[i]), i))
+    return sorted(order[:k])
+
+
+def select(sp: StageParams, mask, pred, conf, prev_pred):
+    """The per-step rule of one sequence.  Returns (commit positions in
+    ascending order, e_cand or -1, leftmost masked position of the window or -1)."""
+    conf = np.asarray(conf, dtype=np.float32)
+    lo, hi = sp.window()
+    cands = [i for i in range(max(lo, 0), min(hi, len(mask) - 1) + 1) if mask[i]]
+    first_masked = cands[0] if cands else -1
+
+    # End point of convergence (eq. 6): the furthest position above tau_min.
+    above = [i for i in cands if conf[i] > np.float32(sp.tau_min_conf)]
+    e_cand = max(above) if above else -1
+
+    if sp.stage == SLOW:
+        # Cautious decoding: the top-k_slow confidences of the window.
+        commit = top_k(cands, conf, sp.top_k)
+    elif sp.stage == FAST:
+        # In-span parallel decoding (eq. 9) ...
+        s_high = [i for i in cands
+                  if conf[i] > np.float32(sp.tau_high_conf)
+                  and (sp.conv_mode == 0 or int(pred[i]) == int(prev_pred[i]))]
+        # ... else the fallback top-k_fast refinement.
+        commit = s_high if len(s_high) >= 1 else top_k(cands, conf, sp.top_k)
+    else:
+        commit = []
+    return commit, e_cand, first_masked
+
+
+Predictor = Callable[[np.ndarray, np.ndarray], Tuple[np.ndarray, np.ndarray]]
+"""predict(tokens[B, L], active[B, L]) -> (pred int32 [B, L], conf float32 [B, L]):
+the greedy estimate and its confidence at the active positions."""
+
+
+def step(predict: Predictor, tokens, mask, prev_pred, sps: Sequence[StageParams]):
+    """One denoising step on a batch, in place.  Returns, per sequence,
+    (commit positions, committed tokens, their confidences, e_cand,
+    first_masked, masks left in the sequence)."""
+    B, L = tokens.shape
+    active = np.stack([active_rows(sps[b], mask[b]) for b in range(B)])
+    pred, conf = predict(tokens, active)
+    out = []
+    for b in range(B):
+        commit, e_cand, first_masked = select(sps[b], mask[b], pred[b], conf[b], prev_pred[b])
+        toks = [int(pred[b, i]) for i in commit]
+        cfs = [float(conf[b, i]) for i in commit]
+        for i in commit:                       # transition: unmask, never re-mask
+            tokens[b, i] = pred[b, i]
+            mask[b, i] = 0
+        for i in range(L):                     # remember this step's estimate
+            if active[b, i]:
+                prev_pred[b, i] = pred[b, i]
+        out.append((commit, toks, cfs, e_cand, first_masked, int(mask[b].sum())))
+    return out
+
+
+@dataclass
+class Controller:
+    """Stage controller of one sequence (Algorithm 1's outer loop as a state
+    machine: ask `next_params`, run the step, report back with `observe`)."""
+    gen_start: int
+    gen_end: int
+    p: DecodeParams
+    s_cycle: int = field(init=False)
+    e_cycle: int = field(init=False)
+    stage: int = field(init=False, default=SLOW)
+    history: List[int] = field(init=False, default_factory=list)
+    step_count: int = field(init=False, default=0)   # steps of this slow stage
+    steps: int = field(init=False, default=0)        # N - k
+    log: List[Tuple[int, int, int]] = field(init=False, default_factory=list)
+
+    def __post_init__(self):
+        self.s_cycle = self.gen_start
+        self.e_cycle = self.gen_end - 1
+
+    def next_params(self, mask) -> Optional[StageParams]:
+        if not np.any(mask) or self.steps >= self.p.max_steps:
+            return None
+        slow = self.stage == SLOW
+        return StageParams(self.stage, self.s_cycle, self.e_cycle if not slow else self.gen_end - 1,
+                           self.p.k_slow if slow else self.p.k_fast,
+                           self.p.tau_min_conf, self.p.tau_high_conf, self.p.conv_mode,
+                           self.gen_start, self.gen_end)
+
+    def _start_slow(self):
+        self.stage, self.history, self.step_count = SLOW, [], 0
+
+    def _enter_fast(self, e, mask):
+        e = min(max(e, self.s_cycle), self.gen_end - 1)
+        self.e_cycle = e
+        if np.any(mask[self.s_cycle:e + 1]):
+            self.stage = FAST
+        else:                                   # span already clean: next cycle
+            self.s_cycle = e + 1
+            self._start_slow()
+
+    def observe(self, e_cand: int, first_masked: int, mask_after) -> None:
+        self.steps += 1
+        self.log.append((self.stage, self.s_cycle, self.e_cycle))
+        if self.stage == SLOW:
+            self.step_count += 1
+            e_k = e_cand if e_cand >= 0 else first_masked
+            self.history = (self.history + [e_k])[-self.p.w_hist:]
+            var = float(np.var(np.asarray(self.history, dtype=np.float64)))   # population
+            if len(self.history) >= self.p.w_hist and var < self.p.sigma2_stable:
+                self._enter_fast(sum(self.history) // len(self.history), mask_after)
+            elif self.step_count >= self.p.k_max:
+                self._enter_fast(e_k, mask_after)
+        else:
+            if not np.any(mask_after[self.s_cycle:self.e_cycle + 1]):
+                self.s_cycle = self.e_cycle + 1
+                self._start_slow()
+
+
+def decode(predict: Predictor, tokens, mask, gen_start: int, gen_end: int, p: DecodeParams,
+           trace: Optional[list] = None) -> int:
+    """Full SlowFast decode of a batch, in place; returns the number of
+    denoising steps (forward passes) taken.  Sequences are independent; one
+    shared forward serves every sequence that still has work."""
+    B, L = tokens.shape
+    prev_pred = np.full((B, L), -1, dtype=np.int32)
+    ctl = [Controller(gen_start, gen_end, p) for _ in range(B)]
+    steps = 0
+    while True:
+        sps, live = [], False
+        for b in range(B):
+            sp = ctl[b].next_params(mask[b])
+            if sp is None:
+                sp = StageParams(IDLE, 0, -1, 1, p.tau_min_conf, p.tau_high_conf, p.conv_mode,
+                                 gen_start, gen_end)
+            else:
+                live = True
+            sps.append(sp)
+        if not live:
+            return steps
+        res = step(predict, tokens, mask, prev_pred, sps)
+        steps += 1
+        for b in range(B):
+            if sps[b].stage != IDLE:
+                ctl[b].observe(res[b][3], res[b][4], mask[b])
+        if trace is not None:
+            trace.append((sps, res))
