@@ -1,0 +1,197 @@
+"""Benchmark of the denoising step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llada8b]
+
+A "step" is one pass of the whole hot path (forward over all positions, row
+phase, selection, transition) through dllm_step on a synthetic batch that is
+resident in HBM.  Prints ONE JSON line.  The headline value is tokens processed
+per denoising step per second, B * L / t_step, on the LLaDA-8B-shaped workload
+(batch 1, 256 prompt + 256 masked positions).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0              # MI355X HBM3E
+
+
+def step_flops(cfg, B, L):
+    """Algorithmic flops of one forward: GEMMs 2*M*(nL*(4d^2 + 3df) + dV) plus attention 4*nL*B*L^2*d."""
+    d, f, V, nl = cfg["d_model"], cfg["d_ffn"], cfg["vocab"], cfg["n_layers"]
+    M = B * L
+    return 2.0 * M * (nl * (4 * d * d + 3 * d * f) + d * V) + 4.0 * nl * B * L * L * d
+
+
+def to_bits(t):
+    import torch
+    return t.detach().cpu().contiguous().view(torch.uint16).numpy()
+
+
+def cpu_baseline_step(cfg, weights, tokens):
+    """The oracle, as it stands, on a bounded sample of the same step: 1 of the
+    n_layers layers plus the vocabulary projection and row phase of 32 of the
+    B*L rows; scaled linearly to the whole step."""
+    import numpy as np
+    import oracle
+    from paper_2506_10848_amd import synth
+    B, L = tokens.shape
+    M = B * L
+    n_rows = min(32, M)
+    rows = np.linspace(0, M - 1, n_rows).astype(np.int32)
+    nl = cfg["n_layers"]
+    tok = tokens.cpu().numpy()
+
+    def weights_for(layers):
+        w = {k: to_bits(weights[k]) for k in ("embed", "lm_head", "final_norm")}
+        for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down"):
+            w[k] = [to_bits(weights[k][l]) for l in range(layers)]
+        return w
+
+    mc = synth.model_config(cfg)
+    w1 = weights_for(min(1, nl))
+    t0 = time.perf_counter()
+    lg = oracle.forward(dict(mc, n_layers=0), dict(w1, **{k: [] for k in
+                        ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")}), tok, rows=rows)
+    oracle.row_phase(oracle.round_to_bf16(lg), mc["mask_id"])
+    t_head = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.forward(dict(mc, n_layers=min(1, nl)), w1, tok, rows=rows)
+    t_one = time.perf_counter() - t0
+    t_layer = max(t_one - t_head, 0.0)
+    t_step = nl * t_layer + t_head * (M / n_rows)
+    return dict(value=M / t_step, unit="tokens/s", cores=oracle.threads(), kind="oracle",
+                sample=f"1 of {nl} layers over all {M} rows ({t_layer:.2f} s) + vocabulary projection and row phase "
+                       f"of {n_rows} of {M} rows ({t_head:.2f} s), scaled linearly to a whole step ({t_step:.1f} s)")
+
+
+def selector_extra(b, synth, torch):
+    """Selector microbenchmark (16 x 2048 x 126464 bf16 logits, 50 % masked rows):
+    achieved HBM bandwidth on the algorithmic bytes (masked rows only)."""
+    cfg = synth.CONFIGS["selector"]
+    B, L, V = cfg["batch"], cfg["seq"], cfg["vocab"]
+    logits, mask, planted, agree, other = synth.make_selector_inputs(cfg, "cuda")
+    tokens = torch.full((B, L), cfg["mask_id"], dtype=torch.int32, device="cuda")
+    prev = torch.where(agree, planted, other).to(torch.int32)
+    pred = torch.empty((B, L), dtype=torch.int32, device="cuda")
+    conf = torch.empty((B, L), dtype=torch.float32, device="cuda")
+    out = b.CommitList(B, L)
+    sps = [b.stage_params(b.STAGE_SLOW, 0, L - 1, 1, 0.1, 0.9, 1, 0, L) for _ in range(B)]
+    n_masked = int(mask.sum())
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    times = []
+    for it in range(8):
+        m = mask.clone(); p = prev.clone(); t = tokens.clone()
+        torch.cuda.synchronize()
+        ev[0].record()
+        b.select(logits, t, m, p, sps, cfg["mask_id"], pred, conf, out)
+        ev[1].record()
+        torch.cuda.synchronize()
+        times.append(ev[0].elapsed_time(ev[1]))
+    ms = sorted(times[2:])[len(times[2:]) // 2]
+    bytes_alg = n_masked * V * 2.0
+    del logits
+    return dict(workload="selector 16x2048x126464 bf16, 50% masked, slow stage k=1", ms=ms,
+                masked_rows=n_masked, achieved_GBs=bytes_alg / ms / 1e6, frac_hbm=bytes_alg / ms / 1e6 / HBM_PEAK_GBS)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llada8b", choices=["llada8b", "medium", "tiny"])
+    ap.add_argument("--no-extras", action="store_true", help="skip decode / selector / cpu baseline legs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2506_10848_amd import binding as b
+    from paper_2506_10848_amd import synth
+
+    b.lib()  # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = synth.CONFIGS[args.workload]
+    mc = synth.model_config(cfg)
+    B, P, G = cfg["batch"], cfg["prompt"], cfg["gen"]
+    L = P + G
+    weights = synth.make_weights(cfg, device="cuda")
+    tokens0, mask0, prev0 = synth.make_state(cfg, device="cuda")
+    model = b.Model(mc, weights, B, L)
+    out = b.CommitList(B, L)
+    # first steps of a decode: slow stage over the whole generated region, k_slow = 1
+    sps = [b.stage_params(b.STAGE_SLOW, P, L - 1, 1, 0.1, 0.9, 1, P, L) for _ in range(B)]
+    assert args.steps + args.warmup <= G, "every timed step must still find a masked position"
+
+    tokens, mask, prev = tokens0.clone(), mask0.clone(), prev0.clone()
+    for _ in range(args.warmup):
+        model.step(tokens, mask, prev, sps, out)
+    torch.cuda.synchronize()
+    model.profile_begin(args.steps * mc["n_layers"])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        model.step(tokens, mask, prev, sps, out)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    k_ms, k_launches = model.profile_end()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    assert int(mask.sum()) == B * G - B * (args.steps + args.warmup), "every step must commit one token per sequence"
+
+    flops = step_flops(mc, B, L)
+    k_flops = 2.0 * B * L * mc["d_model"] * 2 * mc["d_ffn"]          # one gate/up GEMM launch
+    k_avg_ms = k_ms / max(k_launches, 1)
+    achieved = k_flops / (k_avg_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_gateup_gemm.json")
+    if args.workload == "llada8b" and os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+
+    result = {
+        "metric": "tokens/s per denoising step (B*L/t_step), LLaDA-8B shape L=512",
+        "value": B * L / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {mc['n_layers']} layers d={mc['d_model']} H={mc['n_heads']}x"
+                               f"{mc['head_dim']} ffn={mc['d_ffn']} V={mc['vocab']}, batch {B}, {P} prompt + {G} "
+                               f"masked (L={L}), seeded N(0,0.02) bf16 weights, slow stage k_slow=1",
+                   "global_batch": B, "seq_len": L},
+        "step_tflops": flops / 1e12,
+        "step_mfma_frac": flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "roofline": {"kernel": "gemm_kernel<..., SwiGLU> (gate/up projection, one launch per layer)",
+                     "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+                     "avg_launch_ms": k_avg_ms, "launches": k_launches, "flops_per_launch": k_flops},
+    }
+
+    if not args.no_extras:
+        # end-to-end generated tokens/s of a full SlowFast decode (paper's TPS definition)
+        tokens, mask = tokens0.clone(), mask0.clone()
+        dp = b.DecodeParams(10 ** 6, 8, 2, 1, 1, 1, 1.0, 0.1, 0.9)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        steps, _ = model.decode(tokens, mask, P, dp)
+        t_dec = time.perf_counter() - t0
+        result["decode"] = {"generated_tokens_per_s": B * G / t_dec, "steps": steps, "seconds": t_dec,
+                            "params": "tau_min 0.1, tau_high 0.9, K_max 8, W_hist 2, sigma2 1.0, k_slow=k_fast=1, conv_mode 1"}
+        result["cpu_baseline"] = cpu_baseline_step(mc, weights, tokens0)
+        model.close()
+        del model, weights
+        torch.cuda.empty_cache()
+        result["selector"] = selector_extra(b, synth, torch)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,225 @@
+/*
+ * dllm.h -- C ABI of the MI355X (gfx950) SlowFast-sampling library.
+ *
+ * One denoising step of a masked-diffusion LLM (Section 3.1 of the paper:
+ * the mask predictor's full-sequence forward, eq. 2; greedy decode, eq. 3;
+ * confidence, the equation of "Low-Confidence Remasking") followed by the
+ * SlowFast selection rule (Section 3.3, eqs. 6 and 9, Algorithm 1), plus the
+ * stage controller and decode loop of Algorithm 1.
+ *
+ * Conventions
+ *   - Every function returns DLLM_OK (0) or a negative dllm_status.  Nothing
+ *     throws across this boundary.  A textual reason for the last failure of a
+ *     handle is kept in the handle (dllm_last_error); for handle-free functions
+ *     it is kept per thread (dllm_last_error(NULL)).
+ *   - "dev" pointers are HIP device memory on the device that was current at
+ *     dllm_create; "host" pointers are ordinary host memory.
+ *   - All device work is enqueued on the HIP stream given at dllm_create (or
+ *     passed to the handle-free functions).  Calls return without waiting
+ *     unless stated otherwise.  The library creates no streams of its own.
+ *   - The caller owns tokens / mask / prev_pred / commit lists / weights and
+ *     keeps them alive while work that uses them is in flight.  The library
+ *     owns its workspace (activations, logits, per-position predictions).
+ *   - Matrices are row-major bf16.  A linear map is stored as W[N][K] and
+ *     applied as y = x W^T.
+ *   - Positions are absolute, 0-based, over prompt + generated region.  A span
+ *     [s, e] is inclusive at both ends; the generated region is
+ *     [gen_start, gen_end).
+ */
+#ifndef DLLM_H
+#define DLLM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DLLM_OK = 0,
+    DLLM_EINVAL = -1,    /* bad argument: null pointer, shape, range                 */
+    DLLM_ENOMEM = -2,    /* device or host allocation failed                         */
+    DLLM_EHIP = -3,      /* a HIP runtime call or kernel launch failed               */
+    DLLM_ECAPACITY = -4, /* commit list capacity smaller than the step's window      */
+    DLLM_ESTATE = -5     /* call not valid in the handle's current state             */
+} dllm_status;
+
+enum { DLLM_STAGE_SLOW = 0, DLLM_STAGE_FAST = 1, DLLM_STAGE_IDLE = 2 };
+
+#define DLLM_MAX_BATCH 64
+
+typedef struct dllm_handle dllm_handle; /* opaque, owned by the library */
+
+/* Shape of the mask predictor.  The paper only calls it a bidirectional
+ * Transformer (Section 2.1); the operator stack is LLaDA-style: pre-norm
+ * RMSNorm, rotate-half RoPE on q and k, non-causal multi-head attention with
+ * scale 1/sqrt(head_dim), SwiGLU feed-forward, untied vocabulary projection,
+ * no biases.  Requires n_heads * head_dim == d_model, head_dim in {64, 128},
+ * d_model % 8 == 0, d_ffn % 8 == 0, vocab % 8 == 0, 0 <= mask_id < vocab,
+ * 1 <= max_batch <= DLLM_MAX_BATCH, 1 <= max_seq <= 8192. */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab, mask_id;
+    float rms_eps, rope_theta;
+    int32_t max_batch, max_seq;
+} dllm_config;
+
+/* Device pointers to bf16 weights; the library reads them in place and never
+ * copies or frees them.  Per-layer members are host arrays of n_layers device
+ * pointers (the arrays themselves are copied at create).
+ *   embed      [vocab][d_model]     token embedding ([MASK] has its own row)
+ *   lm_head    [vocab][d_model]
+ *   final_norm [d_model]
+ *   attn_norm  [d_model]            gain of the norm before attention
+ *   wqkv       [3 d_model][d_model] rows: q features | k features | v features,
+ *                                   each head-major (h * head_dim + j)
+ *   wo         [d_model][d_model]
+ *   ffn_norm   [d_model]
+ *   w_gate_up  [2 d_ffn][d_model]   rows: gate | up
+ *   w_down     [d_model][d_ffn] */
+typedef struct {
+    const void *embed, *lm_head, *final_norm;
+    const void *const *attn_norm, *const *wqkv, *const *wo, *const *ffn_norm, *const *w_gate_up, *const *w_down;
+} dllm_weights;
+
+/* What one step needs to know about one sequence (Section 3.3).
+ *   slow stage: the window is [s_cycle, gen_end - 1]; the step commits the
+ *     top_k (= k_slow) most confident masked positions of the window
+ *     ("Cautious Decoding") and reports e_cand (eq. 6).
+ *   fast stage: the window is [s_cycle, e_cycle]; the step commits every masked
+ *     position of the window whose confidence exceeds tau_high_conf (eq. 9),
+ *     or, if there is none, the top_k (= k_fast) most confident ones
+ *     ("Fallback Top-k Refinement").
+ *   idle: the sequence rides along in the forward; nothing is selected.
+ *   conv_mode 0: Algorithm 1 as printed.  1: a position joins the fast set only
+ *     if its prediction equals prev_pred (Convergence Principle, Section 3.2).
+ * Ranking is by (higher confidence, then lower position); thresholds are
+ * strict ">"; every comparison is made on binary32 confidences. */
+typedef struct {
+    int32_t stage;
+    int32_t s_cycle, e_cycle;
+    int32_t top_k;
+    float tau_min_conf, tau_high_conf;
+    int32_t conv_mode;
+    int32_t gen_start, gen_end;
+} dllm_stage_params;
+
+/* Result of a step, all members dev pointers, caller-allocated.
+ *   n_commit       [B]            committed positions of this step
+ *   pos, tok, conf [B][capacity]  the commits, ascending position
+ *   e_cand         [B]            eq. 6 over the window, -1 if no masked position
+ *                                 of the window exceeds tau_min_conf
+ *   first_masked   [B]            leftmost masked position of the window before
+ *                                 the commit, -1 if none
+ *   n_masked_after [B]            masked positions left in the whole sequence
+ * capacity must be >= the longest window of the batch. */
+typedef struct {
+    int32_t capacity;
+    int32_t *n_commit;
+    int32_t *pos, *tok;
+    float *conf;
+    int32_t *e_cand, *first_masked, *n_masked_after;
+} dllm_commit_list;
+
+/* Inputs of Algorithm 1 ("Require" line) plus the k_slow / k_fast the paper
+ * leaves open. */
+typedef struct {
+    int32_t max_steps; /* N */
+    int32_t k_max, w_hist;
+    int32_t k_slow, k_fast;
+    int32_t conv_mode;
+    float sigma2_stable, tau_min_conf, tau_high_conf;
+} dllm_decode_params;
+
+/* One record per denoising step of dllm_decode. */
+typedef struct {
+    int32_t n_slow, n_fast, n_idle; /* sequences in each stage during the step */
+    int32_t n_commit;               /* tokens committed by the step, whole batch */
+    float ms;                       /* device time of the step (HIP events)      */
+} dllm_step_stat;
+
+/* Validates the configuration, records the weight pointers and allocates the
+ * workspace for max_batch x max_seq on the current device.  `hip_stream` is a
+ * hipStream_t (NULL = the default stream).  Synchronous. */
+int dllm_create(const dllm_config *cfg, const dllm_weights *w, void *hip_stream, dllm_handle **out);
+void dllm_destroy(dllm_handle *h);
+const char *dllm_last_error(const dllm_handle *h);
+
+/* One denoising step on a batch (Section 3.1 eqs. 2-5 + Section 3.3):
+ * forward over all B*L positions, greedy decode and confidence at the masked
+ * positions of each window, selection, and the transition
+ *   tokens[pos] <- prediction, mask[pos] <- 0            at committed positions
+ *   prev_pred[i] <- prediction                           at every masked position of the window
+ * Committed tokens are never re-masked.  Logits never leave the library.
+ *   tokens    dev int32 [B][L]  in/out
+ *   mask      dev uint8 [B][L]  in/out, 1 = [MASK]
+ *   prev_pred dev int32 [B][L]  in/out, -1 = no previous prediction
+ *   sp        host [B]
+ *   out       host struct of dev pointers
+ * Errors (nothing is enqueued): null pointers, B or L out of range, a window
+ * outside [gen_start, gen_end), e_cycle < s_cycle in the fast stage, top_k < 1,
+ * capacity below the longest window.  A sequence without masked positions in
+ * its window is not an error: n_commit = 0. */
+int dllm_step(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *mask, int32_t *prev_pred,
+              const dllm_stage_params *sp, const dllm_commit_list *out);
+
+/* Full SlowFast decode (Algorithm 1) of B sequences that share gen_start and
+ * gen_end = L: alternates exploratory (slow) and accelerated (fast) stages per
+ * sequence until no [MASK] is left or max_steps steps were taken.  The stage
+ * controller runs on the host and reads a few integers per sequence back after
+ * every step, so this call is synchronous.  tokens / mask as in dllm_step.
+ *   steps_taken host out, number of forward passes
+ *   stats       host out, nullable, up to stats_capacity records */
+int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t *tokens, uint8_t *mask,
+                const dllm_decode_params *p, int32_t *steps_taken, dllm_step_stat *stats, int32_t stats_capacity);
+
+/* Test and measurement hooks: device pointers into the workspace, valid until
+ * the next call on the handle.  logits: bf16 [B*L][vocab] of the last forward;
+ * pred / conf: int32 / float [B*L] of the last row phase (defined at the
+ * masked positions of each window only). */
+int dllm_debug_logits(dllm_handle *h, const void **logits);
+int dllm_debug_rows(dllm_handle *h, const int32_t **pred, const float **conf);
+
+/* Measurement hook for the kernel that carries the most flops of a step, the
+ * gate/up projection GEMM with the SwiGLU epilogue (one launch per layer):
+ * between begin and end every such launch is bracketed by a HIP event pair on
+ * the handle's stream, up to max_launches pairs.  dllm_profile_end waits for
+ * the stream, returns the summed device time of the bracketed launches and
+ * their number, and switches the hook off. */
+int dllm_profile_begin(dllm_handle *h, int32_t max_launches);
+int dllm_profile_end(dllm_handle *h, float *total_ms, int32_t *launches);
+
+/* Forward only (eq. 2): fills the logits workspace for tokens dev int32 [B][L]. */
+int dllm_forward(dllm_handle *h, int32_t B, int32_t L, const int32_t *tokens);
+
+/* The selector alone, on logits the caller provides (eq. 3, the confidence
+ * equation, Section 3.3): row phase over the masked positions of each window,
+ * then selection and the transition of dllm_step.
+ *   logits dev bf16 [B][L][V]; pred / conf dev [B][L] outputs (written at the
+ *   masked positions of each window); the rest as in dllm_step.
+ * `hip_stream` as in dllm_create.  Requires 0 <= mask_id < V, B <= DLLM_MAX_BATCH,
+ * L <= 8192. */
+int dllm_select(void *hip_stream, const void *logits, int32_t B, int32_t L, int32_t V, int32_t mask_id,
+                int32_t *tokens, uint8_t *mask, int32_t *prev_pred, const dllm_stage_params *sp,
+                int32_t *pred, float *conf, const dllm_commit_list *out);
+
+/* ---- building blocks, exposed for per-kernel parity tests and timing -------
+ * All pointers dev; all enqueue on `hip_stream`; shapes are validated.        */
+
+/* C[M][N] (bf16) = A[M][K] (bf16) * W[N][K]^T, fp32 accumulation.  K % 8 == 0. */
+int dllm_op_linear(void *hip_stream, const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K);
+/* out[M][f] = silu(A Wg^T) * (A Wu^T) with W = [gate | up] rows, [2f][K]. */
+int dllm_op_linear_swiglu(void *hip_stream, const void *A, const void *W, void *out, int32_t M, int32_t f,
+                          int32_t K);
+/* x (fp32 [M][d], in/out) += sum of n_partials fp32 [M][d] slabs (may be 0);
+ * h (bf16 [M][d]) = RMSNorm(x) * gain. */
+int dllm_op_add_rmsnorm(void *hip_stream, float *x, const float *partials, int32_t n_partials,
+                        const void *gain, void *h, int32_t M, int32_t d, float eps);
+/* In-place RoPE on the q and k thirds of qkv bf16 [B*L][3*H*dh]. */
+int dllm_op_rope(void *hip_stream, void *qkv, int32_t B, int32_t L, int32_t H, int32_t dh, float theta);
+/* Non-causal attention: qkv bf16 [B*L][3*H*dh] -> out bf16 [B*L][H*dh]. */
+int dllm_op_attention(void *hip_stream, const void *qkv, void *out, int32_t B, int32_t L, int32_t H, int32_t dh);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLLM_H */

@@ -136,9 +136,10 @@ def swiglu(gate, up):
     return out
 
 
-def forward(cfg: dict, weights: dict, tokens):
+def forward(cfg: dict, weights: dict, tokens, rows=None):
     """cfg: dict with the orc_config fields; weights: dict of uint16 arrays
-    (per-layer entries are lists).  tokens [B, L] -> logits float64 [B*L, V]."""
+    (per-layer entries are lists).  tokens [B, L] -> logits float64 [B*L, V],
+    or [len(rows), V] when `rows` (indices into B*L) is given."""
     c = _Config(*[int(cfg[k]) for k in
                   ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab", "mask_id")],
                 float(cfg["rms_eps"]), float(cfg["rope_theta"]))
@@ -161,8 +162,13 @@ def forward(cfg: dict, weights: dict, tokens):
                    ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")])
     tokens = np.ascontiguousarray(tokens, dtype=np.int32)
     B, L = tokens.shape
-    logits = np.empty((B * L, c.vocab), dtype=np.float64)
-    rc = lib().orc_forward(C.byref(c), C.byref(w), _p(tokens), C.c_int(B), C.c_int(L), _p(logits))
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, dtype=np.int32)
+    n_out = B * L if rows is None else rows.shape[0]
+    logits = np.empty((n_out, c.vocab), dtype=np.float64)
+    rc = lib().orc_forward(C.byref(c), C.byref(w), _p(tokens), C.c_int(B), C.c_int(L),
+                           _p(rows) if rows is not None else None, C.c_int(0 if rows is None else rows.shape[0]),
+                           _p(logits))
     if rc != 0:
         raise ValueError(f"orc_forward failed with {rc}")
     return logits

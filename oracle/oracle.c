@@ -184,8 +184,12 @@ void orc_swiglu(const double *gate, const double *up, int64_t n, double *out)
 
 /* Full forward of the mask predictor (Section 3.1, eq. 2): token ids
  * [B][L] -> logits [B*L][vocab] in double.  Pre-norm residual blocks, no
- * biases, positions 0..L-1 inside each sequence, no attention mask. */
-int orc_forward(const orc_config *c, const orc_weights *w, const int32_t *tokens, int B, int L, double *logits)
+ * biases, positions 0..L-1 inside each sequence, no attention mask.
+ * If rows != NULL only the n_rows listed rows (indices into B*L) get a
+ * vocabulary projection and logits is [n_rows][vocab]; the layers always run
+ * on every position. */
+int orc_forward(const orc_config *c, const orc_weights *w, const int32_t *tokens, int B, int L,
+                const int32_t *rows, int n_rows, double *logits)
 {
     const int d = c->d_model, H = c->n_heads, dh = c->head_dim, f = c->d_ffn;
     if (H * dh != d) return -1;
@@ -242,7 +246,15 @@ int orc_forward(const orc_config *c, const orc_weights *w, const int32_t *tokens
         for (int64_t i = 0; i < M * d; ++i) x[i] += proj[i];
     }
     orc_rmsnorm(x, w->final_norm, M, d, c->rms_eps, h);
-    orc_linear(h, w->lm_head, M, d, c->vocab, logits);
+    if (rows) {
+        for (int i = 0; i < n_rows; ++i) {
+            if (rows[i] < 0 || rows[i] >= M) return -4;
+            memcpy(x + (int64_t)i * d, h + (int64_t)rows[i] * d, sizeof(double) * d);
+        }
+        orc_linear(x, w->lm_head, n_rows, d, c->vocab, logits);
+    } else {
+        orc_linear(h, w->lm_head, M, d, c->vocab, logits);
+    }
 
     free(x); free(h); free(qkv); free(q); free(k); free(v); free(att); free(proj);
     free(gu); free(gate); free(up); free(act); free(pos);

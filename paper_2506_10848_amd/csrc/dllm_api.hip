@@ -1,0 +1,559 @@
+// C ABI layer: argument validation, workspace, the forward pass wiring, the
+// step (forward + selector) and the host-side stage controller of Algorithm 1.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "internal.h"
+
+using namespace dllm;
+
+namespace {
+
+thread_local std::string g_err;
+
+struct Workspace {
+    float *x = nullptr;          // residual stream fp32 [M][d]
+    uint16_t *h = nullptr;       // normalised activations bf16 [M][d]
+    uint16_t *qkv = nullptr;     // [M][3d]
+    uint16_t *att = nullptr;     // [M][d]
+    uint16_t *act = nullptr;     // [M][f]
+    float *partials = nullptr;   // split-K slabs fp32 [kMaxSplits][M][d]
+    uint16_t *logits = nullptr;  // [M][V]
+    int32_t *pred = nullptr;     // [M]
+    float *conf = nullptr;       // [M]
+    float2 *rope = nullptr;      // [max_seq][dh/2]
+    // decode-only state
+    int32_t *prev_pred = nullptr;  // [M]
+    int32_t *cl_ints = nullptr;    // n_commit, e_cand, first_masked, n_masked_after: 4 x [max_batch]
+    int32_t *cl_pos = nullptr, *cl_tok = nullptr;
+    float *cl_conf = nullptr;      // [max_batch][max_seq]
+    uint8_t *host_pinned = nullptr;
+};
+constexpr int kMaxSplits = 8;
+
+}  // namespace
+
+struct dllm_handle {
+    dllm_config cfg;
+    hipStream_t stream;
+    const void *embed, *lm_head, *final_norm;
+    std::vector<const void *> attn_norm, wqkv, wo, ffn_norm, w_gate_up, w_down;
+    Workspace ws;
+    std::vector<void *> allocs;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    std::string err;
+    int last_B = 0, last_L = 0;
+    // measurement hook: event pairs around the gate/up GEMM launches
+    std::vector<hipEvent_t> prof_ev;
+    int prof_cap = 0, prof_used = 0;
+    bool prof_on = false;
+};
+
+namespace {
+
+int fail(dllm_handle *h, int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (h) h->err = buf; else g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(h, call)                                                                          \
+    do {                                                                                          \
+        hipError_t e_ = (call);                                                                   \
+        if (e_ != hipSuccess) return fail(h, DLLM_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+template <class T>
+int dev_alloc(dllm_handle *h, T **p, size_t count)
+{
+    void *q = nullptr;
+    if (hipMalloc(&q, count * sizeof(T) + 256) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(h, DLLM_ENOMEM, "device allocation of %zu bytes failed", count * sizeof(T));
+    }
+    h->allocs.push_back(q);
+    *p = static_cast<T *>(q);
+    return DLLM_OK;
+}
+
+// Checks the per-sequence parameters and turns them into kernel windows.
+int build_select_args(dllm_handle *h, int B, int L, const dllm_stage_params *sp, int capacity, SelectArgs *out)
+{
+    if (B < 1 || B > DLLM_MAX_BATCH) return fail(h, DLLM_EINVAL, "batch %d outside [1, %d]", B, DLLM_MAX_BATCH);
+    if (L < 1 || L > 8192) return fail(h, DLLM_EINVAL, "sequence length %d outside [1, 8192]", L);
+    int longest = 0;
+    for (int b = 0; b < B; ++b) {
+        const dllm_stage_params &p = sp[b];
+        SeqWindow &w = out->w[b];
+        w.stage = p.stage; w.top_k = p.top_k; w.tau_min = p.tau_min_conf; w.tau_high = p.tau_high_conf;
+        w.conv_mode = p.conv_mode;
+        if (p.stage == DLLM_STAGE_IDLE) { w.lo = 0; w.hi = -1; continue; }
+        if (p.stage != DLLM_STAGE_SLOW && p.stage != DLLM_STAGE_FAST)
+            return fail(h, DLLM_EINVAL, "sequence %d: unknown stage %d", b, p.stage);
+        if (p.gen_start < 0 || p.gen_end > L || p.gen_start > p.gen_end)
+            return fail(h, DLLM_EINVAL, "sequence %d: generated region [%d, %d) outside [0, %d]", b, p.gen_start,
+                        p.gen_end, L);
+        if (p.top_k < 1) return fail(h, DLLM_EINVAL, "sequence %d: top_k %d < 1", b, p.top_k);
+        if (p.conv_mode != 0 && p.conv_mode != 1)
+            return fail(h, DLLM_EINVAL, "sequence %d: conv_mode %d is not 0 or 1", b, p.conv_mode);
+        w.lo = p.s_cycle;
+        w.hi = p.stage == DLLM_STAGE_SLOW ? p.gen_end - 1 : p.e_cycle;
+        if (p.stage == DLLM_STAGE_FAST && p.e_cycle < p.s_cycle)
+            return fail(h, DLLM_EINVAL, "sequence %d: fast stage with e_cycle %d < s_cycle %d", b, p.e_cycle,
+                        p.s_cycle);
+        if (w.lo < p.gen_start || w.hi >= p.gen_end)
+            return fail(h, DLLM_EINVAL, "sequence %d: window [%d, %d] outside the generated region [%d, %d)", b, w.lo,
+                        w.hi, p.gen_start, p.gen_end);
+        if (w.hi - w.lo + 1 > longest) longest = w.hi - w.lo + 1;
+    }
+    if (capacity < longest)
+        return fail(h, DLLM_ECAPACITY, "commit list capacity %d below the longest window %d", capacity, longest);
+    return DLLM_OK;
+}
+
+int check_commit_list(dllm_handle *h, const dllm_commit_list *o, CommitOut *c)
+{
+    if (!o) return fail(h, DLLM_EINVAL, "commit list is null");
+    if (!o->n_commit || !o->pos || !o->tok || !o->conf || !o->e_cand || !o->first_masked || !o->n_masked_after)
+        return fail(h, DLLM_EINVAL, "commit list has a null member");
+    if (o->capacity < 0) return fail(h, DLLM_EINVAL, "commit list capacity %d < 0", o->capacity);
+    *c = CommitOut{o->capacity, o->n_commit, o->pos, o->tok, o->conf, o->e_cand, o->first_masked, o->n_masked_after};
+    return DLLM_OK;
+}
+
+int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens)
+{
+    const dllm_config &c = h->cfg;
+    const int M = B * L, d = c.d_model, f = c.d_ffn;
+    Workspace &w = h->ws;
+    hipStream_t st = h->stream;
+    HIP_TRY(h, launch_embed(st, tokens, h->embed, w.x, M, d));
+    int pending = 0;  // fp32 slabs waiting to be added to the residual stream
+    for (int l = 0; l < c.n_layers; ++l) {
+        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->attn_norm[l], w.h, M, d, c.rms_eps));
+        HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, h->wqkv[l], w.qkv, M, 3 * d, d));
+        HIP_TRY(h, launch_rope(st, w.qkv, w.rope, B, L, c.n_heads, c.head_dim, c.rope_theta));
+        HIP_TRY(h, launch_attention(st, w.qkv, w.att, B, L, c.n_heads, c.head_dim));
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, M, d, d));
+        pending = gemm_num_splits(M, d, d);
+        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->ffn_norm[l], w.h, M, d, c.rms_eps));
+        const bool prof = h->prof_on && h->prof_used < h->prof_cap;
+        if (prof) HIP_TRY(h, hipEventRecord(h->prof_ev[2 * h->prof_used], st));
+        HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, h->w_gate_up[l], w.act, M, 2 * f, d));
+        if (prof) HIP_TRY(h, hipEventRecord(h->prof_ev[2 * h->prof_used++ + 1], st));
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, h->w_down[l], w.partials, M, d, f));
+        pending = gemm_num_splits(M, d, f);
+    }
+    HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, M, d, c.rms_eps));
+    HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, h->lm_head, w.logits, M, c.vocab, d));
+    h->last_B = B;
+    h->last_L = L;
+    return DLLM_OK;
+}
+
+int check_batch(dllm_handle *h, int B, int L)
+{
+    if (!h) return fail(nullptr, DLLM_EINVAL, "handle is null");
+    if (B < 1 || B > h->cfg.max_batch) return fail(h, DLLM_EINVAL, "batch %d outside [1, %d]", B, h->cfg.max_batch);
+    if (L < 1 || L > h->cfg.max_seq) return fail(h, DLLM_EINVAL, "sequence length %d outside [1, %d]", L, h->cfg.max_seq);
+    return DLLM_OK;
+}
+
+// ---- stage controller (Algorithm 1, outer loop) as a per-sequence state machine
+struct Controller {
+    int gen_start, gen_end;
+    const dllm_decode_params *p;
+    int s_cycle, e_cycle, stage = DLLM_STAGE_SLOW;
+    int step_count = 0, steps = 0;
+    std::vector<int> hist;
+
+    Controller(int gs, int ge, const dllm_decode_params *pp)
+        : gen_start(gs), gen_end(ge), p(pp), s_cycle(gs), e_cycle(ge - 1) {}
+
+    static bool any_mask(const uint8_t *m, int lo, int hi)
+    {
+        for (int i = lo; i <= hi; ++i)
+            if (m[i]) return true;
+        return false;
+    }
+    // false: the sequence is finished (or out of steps)
+    bool next(const uint8_t *mask, int L, dllm_stage_params *sp) const
+    {
+        sp->tau_min_conf = p->tau_min_conf; sp->tau_high_conf = p->tau_high_conf; sp->conv_mode = p->conv_mode;
+        sp->gen_start = gen_start; sp->gen_end = gen_end;
+        if (steps >= p->max_steps || !any_mask(mask, 0, L - 1)) {
+            sp->stage = DLLM_STAGE_IDLE; sp->s_cycle = 0; sp->e_cycle = -1; sp->top_k = 1;
+            return false;
+        }
+        sp->stage = stage;
+        sp->s_cycle = s_cycle;
+        sp->e_cycle = stage == DLLM_STAGE_SLOW ? gen_end - 1 : e_cycle;
+        sp->top_k = stage == DLLM_STAGE_SLOW ? p->k_slow : p->k_fast;
+        return true;
+    }
+    void start_slow() { stage = DLLM_STAGE_SLOW; hist.clear(); step_count = 0; }
+    void enter_fast(int e, const uint8_t *mask)
+    {
+        if (e < s_cycle) e = s_cycle;
+        if (e > gen_end - 1) e = gen_end - 1;
+        e_cycle = e;
+        if (any_mask(mask, s_cycle, e)) {
+            stage = DLLM_STAGE_FAST;
+        } else {  // nothing left in the span: the next cycle starts behind it
+            s_cycle = e + 1;
+            start_slow();
+        }
+    }
+    void observe(int e_cand, int first_masked, const uint8_t *mask_after)
+    {
+        ++steps;
+        if (stage == DLLM_STAGE_SLOW) {
+            ++step_count;
+            const int e_k = e_cand >= 0 ? e_cand : first_masked;
+            hist.push_back(e_k);
+            if ((int)hist.size() > p->w_hist) hist.erase(hist.begin());
+            double mean = 0.0, var = 0.0;
+            long sum = 0;
+            for (int v : hist) { mean += v; sum += v; }
+            mean /= (double)hist.size();
+            for (int v : hist) var += ((double)v - mean) * ((double)v - mean);
+            var /= (double)hist.size();  // population variance (eq. 7)
+            if ((int)hist.size() >= p->w_hist && var < (double)p->sigma2_stable)
+                enter_fast((int)(sum / (long)hist.size()), mask_after);  // floor of the mean (eq. 8)
+            else if (step_count >= p->k_max)
+                enter_fast(e_k, mask_after);  // no convergence: last candidate
+        } else if (!any_mask(mask_after, s_cycle, e_cycle)) {
+            s_cycle = e_cycle + 1;
+            start_slow();
+        }
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+const char *dllm_last_error(const dllm_handle *h) { return h ? h->err.c_str() : g_err.c_str(); }
+
+int dllm_create(const dllm_config *cfg, const dllm_weights *w, void *hip_stream, dllm_handle **out)
+{
+    if (!cfg || !w || !out) return fail(nullptr, DLLM_EINVAL, "dllm_create: null argument");
+    *out = nullptr;
+    const dllm_config &c = *cfg;
+    if (c.n_layers < 0 || c.d_model < 8 || c.n_heads < 1 || c.d_ffn < 8 || c.vocab < 8)
+        return fail(nullptr, DLLM_EINVAL, "dllm_create: non-positive model dimension");
+    if (c.head_dim != 64 && c.head_dim != 128)
+        return fail(nullptr, DLLM_EINVAL, "dllm_create: head_dim %d is not 64 or 128", c.head_dim);
+    if ((long)c.n_heads * c.head_dim != c.d_model)
+        return fail(nullptr, DLLM_EINVAL, "dllm_create: n_heads * head_dim = %ld differs from d_model %d",
+                    (long)c.n_heads * c.head_dim, c.d_model);
+    if (c.d_model % 8 || c.d_ffn % 8 || c.vocab % 8)
+        return fail(nullptr, DLLM_EINVAL, "dllm_create: d_model, d_ffn and vocab must be multiples of 8");
+    if (c.mask_id < 0 || c.mask_id >= c.vocab)
+        return fail(nullptr, DLLM_EINVAL, "dllm_create: mask_id %d outside [0, %d)", c.mask_id, c.vocab);
+    if (c.max_batch < 1 || c.max_batch > DLLM_MAX_BATCH)
+        return fail(nullptr, DLLM_EINVAL, "dllm_create: max_batch %d outside [1, %d]", c.max_batch, DLLM_MAX_BATCH);
+    if (c.max_seq < 1 || c.max_seq > 8192)
+        return fail(nullptr, DLLM_EINVAL, "dllm_create: max_seq %d outside [1, 8192]", c.max_seq);
+    if (!(c.rms_eps >= 0.0f) || !(c.rope_theta > 0.0f))
+        return fail(nullptr, DLLM_EINVAL, "dllm_create: rms_eps must be >= 0 and rope_theta > 0");
+    if (!w->embed || !w->lm_head || !w->final_norm)
+        return fail(nullptr, DLLM_EINVAL, "dllm_create: null embed / lm_head / final_norm");
+    if (c.n_layers > 0 && (!w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm || !w->w_gate_up || !w->w_down))
+        return fail(nullptr, DLLM_EINVAL, "dllm_create: null per-layer weight array");
+    if (!aligned16(w->embed) || !aligned16(w->lm_head) || !aligned16(w->final_norm))
+        return fail(nullptr, DLLM_EINVAL, "dllm_create: weights must be 16-byte aligned");
+
+    dllm_handle *h = new (std::nothrow) dllm_handle();
+    if (!h) return fail(nullptr, DLLM_ENOMEM, "dllm_create: host allocation failed");
+    h->cfg = c;
+    h->stream = static_cast<hipStream_t>(hip_stream);
+    h->embed = w->embed; h->lm_head = w->lm_head; h->final_norm = w->final_norm;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const void *ptrs[6] = {w->attn_norm[l], w->wqkv[l], w->wo[l], w->ffn_norm[l], w->w_gate_up[l], w->w_down[l]};
+        for (const void *p : ptrs)
+            if (!p || !aligned16(p)) {
+                delete h;
+                return fail(nullptr, DLLM_EINVAL, "dllm_create: layer %d has a null or misaligned weight", l);
+            }
+        h->attn_norm.push_back(ptrs[0]); h->wqkv.push_back(ptrs[1]); h->wo.push_back(ptrs[2]);
+        h->ffn_norm.push_back(ptrs[3]); h->w_gate_up.push_back(ptrs[4]); h->w_down.push_back(ptrs[5]);
+    }
+
+    const size_t M = (size_t)c.max_batch * c.max_seq, d = c.d_model, f = c.d_ffn;
+    Workspace &s = h->ws;
+    int rc = DLLM_OK;
+    auto A = [&](int r) { if (rc == DLLM_OK) rc = r; };
+    A(dev_alloc(h, &s.x, M * d));
+    A(dev_alloc(h, &s.h, M * d));
+    A(dev_alloc(h, &s.qkv, M * 3 * d));
+    A(dev_alloc(h, &s.att, M * d));
+    A(dev_alloc(h, &s.act, M * f));
+    A(dev_alloc(h, &s.partials, (size_t)kMaxSplits * M * d));
+    A(dev_alloc(h, &s.logits, M * (size_t)c.vocab));
+    A(dev_alloc(h, &s.pred, M));
+    A(dev_alloc(h, &s.conf, M));
+    A(dev_alloc(h, &s.rope, (size_t)c.max_seq * (c.head_dim / 2)));
+    A(dev_alloc(h, &s.prev_pred, M));
+    A(dev_alloc(h, &s.cl_ints, (size_t)4 * c.max_batch));
+    A(dev_alloc(h, &s.cl_pos, M));
+    A(dev_alloc(h, &s.cl_tok, M));
+    A(dev_alloc(h, &s.cl_conf, M));
+    if (rc == DLLM_OK && hipHostMalloc(reinterpret_cast<void **>(&s.host_pinned), M + 16 * c.max_batch + 64,
+                                       hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        rc = fail(h, DLLM_ENOMEM, "dllm_create: pinned host allocation failed");
+    }
+    if (rc == DLLM_OK && (hipEventCreate(&h->ev0) != hipSuccess || hipEventCreate(&h->ev1) != hipSuccess))
+        rc = fail(h, DLLM_EHIP, "dllm_create: hipEventCreate failed");
+    if (rc == DLLM_OK && launch_rope_table(h->stream, s.rope, c.max_seq, c.head_dim, c.rope_theta) != hipSuccess)
+        rc = fail(h, DLLM_EHIP, "dllm_create: rope table launch failed");
+    if (rc == DLLM_OK && hipStreamSynchronize(h->stream) != hipSuccess)
+        rc = fail(h, DLLM_EHIP, "dllm_create: stream synchronize failed");
+    if (rc != DLLM_OK) {
+        g_err = h->err;
+        dllm_destroy(h);
+        return rc;
+    }
+    *out = h;
+    return DLLM_OK;
+}
+
+void dllm_destroy(dllm_handle *h)
+{
+    if (!h) return;
+    (void)hipStreamSynchronize(h->stream);
+    for (void *p : h->allocs) (void)hipFree(p);
+    if (h->ws.host_pinned) (void)hipHostFree(h->ws.host_pinned);
+    for (hipEvent_t e : h->prof_ev) (void)hipEventDestroy(e);
+    if (h->ev0) (void)hipEventDestroy(h->ev0);
+    if (h->ev1) (void)hipEventDestroy(h->ev1);
+    delete h;
+}
+
+int dllm_forward(dllm_handle *h, int32_t B, int32_t L, const int32_t *tokens)
+{
+    int rc = check_batch(h, B, L);
+    if (rc) return rc;
+    if (!tokens) return fail(h, DLLM_EINVAL, "dllm_forward: tokens is null");
+    return forward_impl(h, B, L, tokens);
+}
+
+int dllm_step(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *mask, int32_t *prev_pred,
+              const dllm_stage_params *sp, const dllm_commit_list *out)
+{
+    int rc = check_batch(h, B, L);
+    if (rc) return rc;
+    if (!tokens || !mask || !prev_pred || !sp) return fail(h, DLLM_EINVAL, "dllm_step: null argument");
+    CommitOut co;
+    if ((rc = check_commit_list(h, out, &co))) return rc;
+    SelectArgs args;
+    if ((rc = build_select_args(h, B, L, sp, out->capacity, &args))) return rc;
+    if ((rc = forward_impl(h, B, L, tokens))) return rc;
+    HIP_TRY(h, launch_row_phase(h->stream, h->ws.logits, B, L, h->cfg.vocab, h->cfg.mask_id, mask, args, h->ws.pred,
+                                h->ws.conf));
+    HIP_TRY(h, launch_seq_phase(h->stream, B, L, tokens, mask, prev_pred, h->ws.pred, h->ws.conf, args, co));
+    return DLLM_OK;
+}
+
+int dllm_select(void *hip_stream, const void *logits, int32_t B, int32_t L, int32_t V, int32_t mask_id,
+                int32_t *tokens, uint8_t *mask, int32_t *prev_pred, const dllm_stage_params *sp, int32_t *pred,
+                float *conf, const dllm_commit_list *out)
+{
+    if (!logits || !tokens || !mask || !prev_pred || !sp || !pred || !conf)
+        return fail(nullptr, DLLM_EINVAL, "dllm_select: null argument");
+    if (V < 1) return fail(nullptr, DLLM_EINVAL, "dllm_select: vocab %d < 1", V);
+    if (mask_id < 0 || mask_id >= V) return fail(nullptr, DLLM_EINVAL, "dllm_select: mask_id %d outside [0, %d)", mask_id, V);
+    if ((reinterpret_cast<uintptr_t>(logits) & 1) != 0) return fail(nullptr, DLLM_EINVAL, "dllm_select: misaligned logits");
+    CommitOut co;
+    int rc;
+    if ((rc = check_commit_list(nullptr, out, &co))) return rc;
+    SelectArgs args;
+    if ((rc = build_select_args(nullptr, B, L, sp, out->capacity, &args))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    HIP_TRY(nullptr, launch_row_phase(st, logits, B, L, V, mask_id, mask, args, pred, conf));
+    HIP_TRY(nullptr, launch_seq_phase(st, B, L, tokens, mask, prev_pred, pred, conf, args, co));
+    return DLLM_OK;
+}
+
+int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t *tokens, uint8_t *mask,
+                const dllm_decode_params *p, int32_t *steps_taken, dllm_step_stat *stats, int32_t stats_capacity)
+{
+    int rc = check_batch(h, B, L);
+    if (rc) return rc;
+    if (!tokens || !mask || !p || !steps_taken) return fail(h, DLLM_EINVAL, "dllm_decode: null argument");
+    if (gen_start < 0 || gen_start > L) return fail(h, DLLM_EINVAL, "dllm_decode: gen_start %d outside [0, %d]", gen_start, L);
+    if (p->max_steps < 0 || p->k_max < 1 || p->w_hist < 1 || p->k_slow < 1 || p->k_fast < 1)
+        return fail(h, DLLM_EINVAL, "dllm_decode: max_steps >= 0, k_max, w_hist, k_slow, k_fast >= 1 required");
+    if (p->conv_mode != 0 && p->conv_mode != 1) return fail(h, DLLM_EINVAL, "dllm_decode: conv_mode must be 0 or 1");
+    if (stats && stats_capacity < 0) return fail(h, DLLM_EINVAL, "dllm_decode: negative stats_capacity");
+
+    Workspace &w = h->ws;
+    const int mb = h->cfg.max_batch;
+    hipStream_t st = h->stream;
+    // prev_pred <- -1 (all bytes 0xff)
+    HIP_TRY(h, hipMemsetAsync(w.prev_pred, 0xff, (size_t)B * L * sizeof(int32_t), st));
+    uint8_t *hmask = w.host_pinned;
+    int32_t *hints = reinterpret_cast<int32_t *>(w.host_pinned + (((size_t)h->cfg.max_batch * h->cfg.max_seq + 63) & ~(size_t)63));
+    HIP_TRY(h, hipMemcpyAsync(hmask, mask, (size_t)B * L, hipMemcpyDeviceToHost, st));
+    HIP_TRY(h, hipStreamSynchronize(st));
+
+    dllm_commit_list cl;
+    cl.capacity = L;
+    cl.n_commit = w.cl_ints; cl.e_cand = w.cl_ints + mb; cl.first_masked = w.cl_ints + 2 * mb;
+    cl.n_masked_after = w.cl_ints + 3 * mb;
+    cl.pos = w.cl_pos; cl.tok = w.cl_tok; cl.conf = w.cl_conf;
+
+    std::vector<Controller> ctl;
+    for (int b = 0; b < B; ++b) ctl.emplace_back(gen_start, L, p);
+    std::vector<dllm_stage_params> sps(B);
+    int steps = 0;
+    for (;;) {
+        bool live = false;
+        int n_slow = 0, n_fast = 0, n_idle = 0;
+        for (int b = 0; b < B; ++b) {
+            live |= ctl[b].next(hmask + (size_t)b * L, L, &sps[b]);
+            n_slow += sps[b].stage == DLLM_STAGE_SLOW;
+            n_fast += sps[b].stage == DLLM_STAGE_FAST;
+            n_idle += sps[b].stage == DLLM_STAGE_IDLE;
+        }
+        if (!live) break;
+        const bool timed = stats && steps < stats_capacity;
+        if (timed) HIP_TRY(h, hipEventRecord(h->ev0, st));
+        if ((rc = dllm_step(h, B, L, tokens, mask, w.prev_pred, sps.data(), &cl))) return rc;
+        if (timed) HIP_TRY(h, hipEventRecord(h->ev1, st));
+        HIP_TRY(h, hipMemcpyAsync(hmask, mask, (size_t)B * L, hipMemcpyDeviceToHost, st));
+        HIP_TRY(h, hipMemcpyAsync(hints, w.cl_ints, (size_t)4 * mb * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        HIP_TRY(h, hipStreamSynchronize(st));
+        int committed = 0;
+        for (int b = 0; b < B; ++b) {
+            if (sps[b].stage == DLLM_STAGE_IDLE) continue;
+            committed += hints[b];
+            ctl[b].observe(hints[mb + b], hints[2 * mb + b], hmask + (size_t)b * L);
+        }
+        if (timed) {
+            float ms = 0.0f;
+            HIP_TRY(h, hipEventElapsedTime(&ms, h->ev0, h->ev1));
+            stats[steps] = dllm_step_stat{n_slow, n_fast, n_idle, committed, ms};
+        }
+        ++steps;
+    }
+    *steps_taken = steps;
+    return DLLM_OK;
+}
+
+int dllm_profile_begin(dllm_handle *h, int32_t max_launches)
+{
+    if (!h) return fail(nullptr, DLLM_EINVAL, "dllm_profile_begin: handle is null");
+    if (max_launches < 1 || max_launches > (1 << 20)) return fail(h, DLLM_EINVAL, "dllm_profile_begin: max_launches outside [1, 2^20]");
+    while ((int)h->prof_ev.size() < 2 * max_launches) {
+        hipEvent_t e;
+        HIP_TRY(h, hipEventCreate(&e));
+        h->prof_ev.push_back(e);
+    }
+    h->prof_cap = max_launches;
+    h->prof_used = 0;
+    h->prof_on = true;
+    return DLLM_OK;
+}
+
+int dllm_profile_end(dllm_handle *h, float *total_ms, int32_t *launches)
+{
+    if (!h || !total_ms || !launches) return fail(h, DLLM_EINVAL, "dllm_profile_end: null argument");
+    if (!h->prof_on) return fail(h, DLLM_ESTATE, "dllm_profile_end: profiling is not enabled");
+    h->prof_on = false;
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    float tot = 0.0f;
+    for (int i = 0; i < h->prof_used; ++i) {
+        float ms = 0.0f;
+        HIP_TRY(h, hipEventElapsedTime(&ms, h->prof_ev[2 * i], h->prof_ev[2 * i + 1]));
+        tot += ms;
+    }
+    *total_ms = tot;
+    *launches = h->prof_used;
+    return DLLM_OK;
+}
+
+int dllm_debug_logits(dllm_handle *h, const void **logits)
+{
+    if (!h || !logits) return fail(h, DLLM_EINVAL, "dllm_debug_logits: null argument");
+    if (h->last_B == 0) return fail(h, DLLM_ESTATE, "dllm_debug_logits: no forward pass has run");
+    *logits = h->ws.logits;
+    return DLLM_OK;
+}
+
+int dllm_debug_rows(dllm_handle *h, const int32_t **pred, const float **conf)
+{
+    if (!h || !pred || !conf) return fail(h, DLLM_EINVAL, "dllm_debug_rows: null argument");
+    if (h->last_B == 0) return fail(h, DLLM_ESTATE, "dllm_debug_rows: no step has run");
+    *pred = h->ws.pred;
+    *conf = h->ws.conf;
+    return DLLM_OK;
+}
+
+// ---- building blocks --------------------------------------------------------
+
+static int check_linear(const void *A, const void *W, const void *C, int M, int N, int K, const char *who)
+{
+    if (!A || !W || !C) return fail(nullptr, DLLM_EINVAL, "%s: null argument", who);
+    if (M < 1 || N < 1 || K < 8 || K % 8) return fail(nullptr, DLLM_EINVAL, "%s: need M, N >= 1 and K a positive multiple of 8", who);
+    if (!aligned16(A) || !aligned16(W) || !aligned16(C)) return fail(nullptr, DLLM_EINVAL, "%s: pointers must be 16-byte aligned", who);
+    return DLLM_OK;
+}
+
+int dllm_op_linear(void *hip_stream, const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K)
+{
+    int rc = check_linear(A, W, C, M, N, K, "dllm_op_linear");
+    if (rc) return rc;
+    HIP_TRY(nullptr, launch_gemm(static_cast<hipStream_t>(hip_stream), kEpiBf16, A, W, C, M, N, K));
+    return DLLM_OK;
+}
+
+int dllm_op_linear_swiglu(void *hip_stream, const void *A, const void *W, void *out, int32_t M, int32_t f, int32_t K)
+{
+    int rc = check_linear(A, W, out, M, f, K, "dllm_op_linear_swiglu");
+    if (rc) return rc;
+    HIP_TRY(nullptr, launch_gemm(static_cast<hipStream_t>(hip_stream), kEpiSwiglu, A, W, out, M, 2 * f, K));
+    return DLLM_OK;
+}
+
+int dllm_op_add_rmsnorm(void *hip_stream, float *x, const float *partials, int32_t n_partials, const void *gain,
+                        void *hout, int32_t M, int32_t d, float eps)
+{
+    if (!x || !gain || !hout || (n_partials > 0 && !partials)) return fail(nullptr, DLLM_EINVAL, "dllm_op_add_rmsnorm: null argument");
+    if (M < 1 || d < 4 || d % 4 || n_partials < 0) return fail(nullptr, DLLM_EINVAL, "dllm_op_add_rmsnorm: need M >= 1, d a positive multiple of 4, n_partials >= 0");
+    if (!aligned16(x) || !aligned16(gain) || !aligned16(hout) || !aligned16(partials)) return fail(nullptr, DLLM_EINVAL, "dllm_op_add_rmsnorm: pointers must be 16-byte aligned");
+    HIP_TRY(nullptr, launch_add_rmsnorm(static_cast<hipStream_t>(hip_stream), x, partials, n_partials, gain, hout, M, d, eps));
+    return DLLM_OK;
+}
+
+int dllm_op_rope(void *hip_stream, void *qkv, int32_t B, int32_t L, int32_t H, int32_t dh, float theta)
+{
+    if (!qkv || !aligned16(qkv)) return fail(nullptr, DLLM_EINVAL, "dllm_op_rope: null or misaligned qkv");
+    if (B < 1 || L < 1 || H < 1 || (dh != 64 && dh != 128) || !(theta > 0.0f)) return fail(nullptr, DLLM_EINVAL, "dllm_op_rope: bad shape");
+    HIP_TRY(nullptr, launch_rope(static_cast<hipStream_t>(hip_stream), qkv, nullptr, B, L, H, dh, theta));
+    return DLLM_OK;
+}
+
+int dllm_op_attention(void *hip_stream, const void *qkv, void *out, int32_t B, int32_t L, int32_t H, int32_t dh)
+{
+    if (!qkv || !out || !aligned16(qkv) || !aligned16(out)) return fail(nullptr, DLLM_EINVAL, "dllm_op_attention: null or misaligned pointer");
+    if (B < 1 || L < 1 || H < 1 || (dh != 64 && dh != 128)) return fail(nullptr, DLLM_EINVAL, "dllm_op_attention: bad shape");
+    if ((long)B > 65535 || (long)H > 65535) return fail(nullptr, DLLM_EINVAL, "dllm_op_attention: B and H must be <= 65535");
+    HIP_TRY(nullptr, launch_attention(static_cast<hipStream_t>(hip_stream), qkv, out, B, L, H, dh));
+    return DLLM_OK;
+}
+
+}  // extern "C"

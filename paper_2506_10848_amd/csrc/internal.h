@@ -1,0 +1,55 @@
+// Internal C++ interface between the C ABI layer and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dllm.h"
+#include "common.h"
+
+namespace dllm {
+
+// Window and rule of one sequence for one step, as the kernels want it.
+struct SeqWindow {
+    int lo, hi;  // inclusive span of positions the step looks at (hi < lo: nothing)
+    int stage;
+    int top_k;
+    float tau_min, tau_high;
+    int conv_mode;
+};
+struct SelectArgs {
+    SeqWindow w[DLLM_MAX_BATCH];
+};
+struct CommitOut {
+    int capacity;
+    int32_t *n_commit, *pos, *tok;
+    float *conf;
+    int32_t *e_cand, *first_masked, *n_masked_after;
+};
+
+hipError_t launch_row_phase(hipStream_t stream, const void *logits, int B, int L, int V, int mask_id,
+                            const uint8_t *mask, const SelectArgs &args, int32_t *pred, float *conf);
+hipError_t launch_seq_phase(hipStream_t stream, int B, int L, int32_t *tokens, uint8_t *mask, int32_t *prev_pred,
+                            const int32_t *pred, const float *conf, const SelectArgs &args, const CommitOut &out);
+
+// ---- forward pass -------------------------------------------------------------
+hipError_t launch_embed(hipStream_t stream, const int32_t *tokens, const void *embed, float *x, int M, int d);
+hipError_t launch_add_rmsnorm(hipStream_t stream, float *x, const float *partials, int n_partials, const void *gain,
+                              void *h, int M, int d, float eps);
+hipError_t launch_rope_table(hipStream_t stream, float2 *table, int max_pos, int dh, float theta);
+// table may be null: angles are then computed in the kernel (slow; test hook)
+hipError_t launch_rope(hipStream_t stream, void *qkv, const float2 *table, int B, int L, int H, int dh, float theta);
+hipError_t launch_attention(hipStream_t stream, const void *qkv, void *out, int B, int L, int H, int dh);
+
+enum GemmEpilogue {
+    kEpiBf16 = 0,     // C bf16 [M][N]
+    kEpiSwiglu = 1,   // W = [gate | up] rows; C bf16 [M][N/2] = silu(gate) * up
+    kEpiPartial = 2,  // C fp32 [splits][M][N], one slab per K split
+};
+// How many K splits launch_gemm will use for a kEpiPartial problem (>= 1).
+int gemm_num_splits(int M, int N, int K);
+// C = A[M][K] * W[N][K]^T.  For kEpiSwiglu N counts gate + up rows.
+hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
+                       int K);
+
+}  // namespace dllm

@@ -295,3 +295,13 @@ def test_row_phase_ties_mask_and_activity():
     assert conf.dtype == np.float32
     assert abs(conf[0] - 1.0 / (3 + 36 * math.exp(-2.5))) < 1e-7
     assert abs(conf[1] - 1.0 / (1 + 38 * math.exp(-1.0))) < 1e-7
+
+
+def test_forward_row_subset_equals_full():
+    cfg = dict(synth.CONFIGS["tiny"], vocab=120, mask_id=119, prompt=4, gen=5, d_model=32, n_heads=2,
+               head_dim=16, d_ffn=40, n_layers=1)
+    w = weights_bits(synth.make_weights(cfg))
+    tokens, _, _ = synth.make_state(cfg, batch=2)
+    full = oracle.forward(synth.model_config(cfg), w, tokens.numpy())
+    rows = [17, 0, 9]
+    assert np.array_equal(oracle.forward(synth.model_config(cfg), w, tokens.numpy(), rows=rows), full[rows])
