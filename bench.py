@@ -110,6 +110,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llada8b", choices=["llada8b", "medium", "tiny"])
     ap.add_argument("--no-extras", action="store_true", help="skip decode / selector / cpu baseline legs")
+    ap.add_argument("--pmc-copy", action="store_true",
+                    help="also launch one plain elementwise copy of 1 GiB (calibrates HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
@@ -174,6 +176,13 @@ def main():
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
                      "avg_launch_ms": k_avg_ms, "launches": k_launches, "flops_per_launch": k_flops},
     }
+
+    if args.pmc_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")          # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     if not args.no_extras:
         # end-to-end generated tokens/s of a full SlowFast decode (paper's TPS definition)
