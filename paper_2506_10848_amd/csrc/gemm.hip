@@ -1,19 +1,33 @@
 // bf16 MFMA GEMM for gfx950:  C = A[M][K] * W[N][K]^T, fp32 accumulation.
 //
-// Both operands are K-contiguous, which is exactly what the 32x32x16 bf16 MFMA
-// wants: a lane feeds 8 consecutive K values of one row (A) or one column (W).
-// A workgroup of 4 waves owns a BM x BN tile; K is walked in steps of 64
-// through double-buffered LDS.  Each 128-byte LDS row is XOR-swizzled in units
-// of 16 bytes (chunk ^= row & 7) so that the 16-byte fragment reads of 8
-// consecutive rows touch all 32 banks once.  Global loads for the next K step
-// are issued before the MFMAs of the current one and land in LDS afterwards.
+// Both operands are K-contiguous, which is what the 32x32x16 bf16 MFMA wants: a
+// lane feeds 8 consecutive K values of one row (A) or one column (W).  A
+// workgroup of 4 waves owns a BM x BN tile and walks K in steps of 64 through a
+// multi-stage LDS ring.
 //
-// Epilogues: bf16 store; SwiGLU (the tile holds the gate and the up columns of
+// Main kernel (gemm_dl_kernel, K % 64 == 0):
+//   * global -> LDS copies are asynchronous (global_load_lds_dwordx4, 1 KB per
+//     wave instruction, no VGPR staging) and run NST-1 K-steps ahead of the math;
+//     the only per-step synchronisation is one s_waitcnt vmcnt + one s_barrier.
+//   * LDS rows are 128 bytes; 16-byte chunks are XOR-swizzled with (row >> 1) & 7.
+//     The LDS has 64 banks and serves 16 lanes x 16 bytes per cycle, i.e. two rows
+//     per cycle, so this keeps the fragment reads of 16 consecutive rows on 64
+//     distinct banks.  The swizzle is applied by choosing which global chunk each
+//     lane copies, because the LDS side of the copy is fixed (lane * 16 bytes).
+//   * fragments for K-substep kk+1 are requested before the MFMAs of substep kk
+//     (scheduling barriers keep the compiler from sinking the reads again).
+//   * MFMAs are issued as (W fragment) x (A fragment): the accumulators then hold
+//     the transposed tile, four consecutive output columns per lane, and the
+//     epilogue stores 8 (bf16) or 16 (fp32) bytes per lane.
+// Fallback kernel (gemm_reg_kernel): any K % 8 == 0, register-staged loads with
+// zero fill, two LDS stages.
+//
+// Epilogues: bf16 store; SwiGLU (a tile carries the gate and the up columns of
 // the same features, so silu(gate) * up is formed in registers); fp32 slabs for
 // split-K, which the next residual-add + RMSNorm kernel sums.
 //
-// Workgroup ids are mapped to tiles so that the workgroups sharing a weight
-// column block run on the same XCD (ids congruent mod 8 share an L2).
+// Workgroup ids are mapped so that the tiles sharing a weight column block run on
+// the same XCD (ids congruent mod 8 share an L2).
 #include <stdlib.h>
 
 #include "internal.h"
@@ -23,8 +37,10 @@ namespace dllm {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kBK = 64;             // K elements per LDS stage
-constexpr int kChunksPerRow = 8;    // 16-byte chunks in a 64-element bf16 row
+constexpr int kBK = 64;           // K elements per LDS stage
+constexpr int kChunksPerRow = 8;  // 16-byte chunks in a 64-element bf16 row
+
+#define DLLM_LDS_VOID(p) ((__attribute__((address_space(3))) void *)(p))
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v)
 {
@@ -33,102 +49,193 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v)
     return c.b;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
-__global__ __launch_bounds__(kThreads) void gemm_kernel(const uint16_t *__restrict__ A,
-                                                        const uint16_t *__restrict__ W, void *__restrict__ Cout,
-                                                        int M, int N, int K, int k_per_split, int num_m, int num_n)
+// Asynchronous 16-byte-per-lane global -> LDS copy; LDS address = m0 + lane * 16.
+// Inline asm on purpose: with the compiler builtin every later LDS read is
+// preceded by a conservative "s_waitcnt vmcnt(0)", which serialises the copy of
+// the next K-steps with the math on the current one.  Waits are placed by hand.
+__device__ __forceinline__ void async_load16(const char *base_uniform, uint32_t voffset, uint32_t lds_addr_uniform)
 {
-    static_assert(WAVES_M * WAVES_N == 4, "4 waves per workgroup");
-    constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
-    constexpr int TM = WTM / 32, TN = WTN / 32;            // 32x32 MFMA tiles per wave
-    static_assert(TM >= 1 && TN >= 1, "wave tile too small");
-    static_assert(EPI != kEpiSwiglu || (TN % 2 == 0), "SwiGLU pairs gate/up sub-tiles");
-    constexpr int A_LOADS = BM * kChunksPerRow / kThreads;
-    constexpr int B_LOADS = BN * kChunksPerRow / kThreads;
-    constexpr int STAGE = (BM + BN) * kChunksPerRow;  // uint4 per stage
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr_uniform), "v"(voffset), "s"(base_uniform)
+                 : "memory");
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const void *p)
+{
+    return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)DLLM_LDS_VOID(p));
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
-    extern __shared__ uint4 smem[];
-
-    // ---- which tile -------------------------------------------------------
-    int pid = blockIdx.x;
-    int pid_m, pid_n;
-    if ((num_n & 7) == 0) {
+// tile of this workgroup; tiles that share W rows get ids congruent mod 8
+__device__ __forceinline__ void tile_of(int pid, int num_m, int num_n, int &pid_m, int &pid_n)
+{
+    const int n8 = num_n & ~7, head = num_m * n8;
+    if (pid < head) {
         const int xcd = pid & 7, j = pid >> 3;
         pid_m = j % num_m;
         pid_n = (j / num_m) * 8 + xcd;
     } else {
-        pid_m = pid % num_m;
-        pid_n = pid / num_m;
+        const int r = pid - head;
+        pid_m = r % num_m;
+        pid_n = n8 + r / num_m;
     }
-    const int m0 = pid_m * BM;
-    // output features per tile column and the W rows behind the LDS B rows
-    constexpr int BN_OUT = (EPI == kEpiSwiglu) ? BN / 2 : BN;
-    const int n0 = pid_n * BN_OUT;
-    const int n_out = (EPI == kEpiSwiglu) ? N / 2 : N;
+}
 
+// Accumulators hold the transposed 32x32 tiles: element e of lane l is output
+// row l % 32, column 8*(e/4) + 4*(l/32) + e%4.
+template <int TM, int TN, int WTM, int WTN, int EPI>
+__device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, int M, int N, int n_out, int m0, int n0,
+                                           int wm, int wn, int l32, int lhalf, int split)
+{
+    constexpr int HALF_TN = TN / 2 > 0 ? TN / 2 : 1;
+    if (EPI == kEpiBf16) {
+        uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = m0 + wm * WTM + i * 32 + l32;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = n0 + wn * WTN + j * 32 + 8 * q + 4 * lhalf;
+                    if (row >= M || col >= N) continue;
+                    uint16_t *p = C + (size_t)row * N + col;
+                    if (col + 3 < N && (N & 3) == 0) {
+                        uint2 w;
+                        w.x = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+                        w.y = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                        *reinterpret_cast<uint2 *>(p) = w;
+                    } else {
+                        for (int e = 0; e < 4 && col + e < N; ++e) p[e] = float_to_bf16_bits(acc[i][j][4 * q + e]);
+                    }
+                }
+        }
+    } else if (EPI == kEpiSwiglu) {
+        uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = m0 + wm * WTM + i * 32 + l32;
+#pragma unroll
+            for (int j = 0; j < HALF_TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = n0 + wn * (WTN / 2) + j * 32 + 8 * q + 4 * lhalf;
+                    float y[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float g = acc[i][j][4 * q + e], u = acc[i][j + HALF_TN][4 * q + e];
+                        y[e] = g / (1.0f + __expf(-g)) * u;
+                    }
+                    if (row >= M || col >= n_out) continue;
+                    uint16_t *p = C + (size_t)row * n_out + col;
+                    if (col + 3 < n_out && (n_out & 3) == 0) {
+                        uint2 w;
+                        w.x = pack_bf16x2(y[0], y[1]);
+                        w.y = pack_bf16x2(y[2], y[3]);
+                        *reinterpret_cast<uint2 *>(p) = w;
+                    } else {
+                        for (int e = 0; e < 4 && col + e < n_out; ++e) p[e] = float_to_bf16_bits(y[e]);
+                    }
+                }
+        }
+    } else {
+        float *C = reinterpret_cast<float *>(Cout) + (size_t)split * M * N;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = m0 + wm * WTM + i * 32 + l32;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = n0 + wn * WTN + j * 32 + 8 * q + 4 * lhalf;
+                    if (row >= M || col >= N) continue;
+                    float *p = C + (size_t)row * N + col;
+                    if (col + 3 < N && (N & 3) == 0) {
+                        *reinterpret_cast<float4 *>(p) = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1],
+                                                                     acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                    } else {
+                        for (int e = 0; e < 4 && col + e < N; ++e) p[e] = acc[i][j][4 * q + e];
+                    }
+                }
+        }
+    }
+}
+
+// LDS row (in 16-byte chunks) of the W fragment j of wave column wn.  For the
+// SwiGLU epilogue the stage holds [gate rows | up rows] and a wave pairs the
+// same features from both halves.
+template <int BM, int BN, int WTN, int TN, int EPI>
+__device__ __forceinline__ int w_frag_row(int j, int wn, int l32)
+{
+    if (EPI == kEpiSwiglu) {
+        constexpr int HALF_TN = TN / 2 > 0 ? TN / 2 : 1;
+        return BM + (j / HALF_TN) * (BN / 2) + wn * (WTN / 2) + (j % HALF_TN) * 32 + l32;
+    }
+    return BM + wn * WTN + j * 32 + l32;
+}
+
+// ---- main kernel: K % 64 == 0, k_per_split % 64 == 0 --------------------------
+template <int BM, int BN, int WM, int WN, int NST, int EPI>
+__global__ __launch_bounds__(kThreads) void gemm_dl_kernel(const uint16_t *__restrict__ A,
+                                                           const uint16_t *__restrict__ W, void *__restrict__ Cout,
+                                                           int M, int N, int K, int k_per_split, int num_m, int num_n)
+{
+    static_assert(WM * WN == 4, "4 waves per workgroup");
+    constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
+    static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 MFMA tiles");
+    static_assert(EPI != kEpiSwiglu || TN % 2 == 0, "SwiGLU pairs gate/up sub-tiles");
+    static_assert(BM % 32 == 0 && BN % 32 == 0 && NST >= 2 && NST <= 4, "stage shape");
+    constexpr int ROWS = BM + BN;      // rows of one stage: the A tile, then the W tile
+    constexpr int LOADS = ROWS / 32;   // 1 KB copies per wave per stage
+    constexpr int A_LOADS = BM / 32;
+    constexpr int STAGE = ROWS * kChunksPerRow;  // uint4 per stage
+    extern __shared__ uint4 smem[];
+
+    int pid_m, pid_n;
+    tile_of(blockIdx.x, num_m, num_n, pid_m, pid_n);
+    constexpr int BN_OUT = (EPI == kEpiSwiglu) ? BN / 2 : BN;
+    const int m0 = pid_m * BM, n0 = pid_n * BN_OUT;
+    const int n_out = (EPI == kEpiSwiglu) ? N / 2 : N;
     const int kbeg = blockIdx.y * k_per_split;
     const int kend = min(K, kbeg + k_per_split);
-    const int nk = (kend - kbeg + kBK - 1) / kBK;
+    const int nk = (kend - kbeg) / kBK;
 
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, lhalf = lane >> 5;
 
-    // ---- global -> register staging ---------------------------------------
-    const int ld_row = tid >> 3, ld_kc = tid & 7;  // + t * 32 rows per extra load
-    const uint16_t *a_ptr[A_LOADS];
-    bool a_ok[A_LOADS];
+    // wave w copies the 8-row groups w, w+4, ...; lane l lands on row l/8, slot l%8
+    // of its group and therefore fetches the chunk that the swizzle puts there
+    const int lrow = lane >> 3;
+    const int kc = (lane & 7) ^ (((wave & 1) << 2) | (lrow >> 1));
+    uint32_t goff[LOADS];  // byte offsets into A (first A_LOADS) or W; rows past the edge are clamped
 #pragma unroll
-    for (int t = 0; t < A_LOADS; ++t) {
-        const int grow = m0 + ld_row + t * 32;
-        a_ok[t] = grow < M;
-        a_ptr[t] = A + (size_t)(a_ok[t] ? grow : 0) * K + ld_kc * 8;
-    }
-    const uint16_t *b_ptr[B_LOADS];
-    bool b_ok[B_LOADS];
-#pragma unroll
-    for (int t = 0; t < B_LOADS; ++t) {
-        const int j = ld_row + t * 32;  // LDS B row
-        int wrow;
-        bool ok;
-        if (EPI == kEpiSwiglu) {
-            const int half = j / (BN / 2), jj = j % (BN / 2);
-            ok = n0 + jj < n_out;
-            wrow = half * n_out + n0 + jj;
+    for (int t = 0; t < LOADS; ++t) {
+        const int r = 8 * (wave + 4 * t) + lrow;
+        int grow;
+        if (t < A_LOADS) {
+            grow = min(m0 + r, M - 1);
+        } else if (EPI == kEpiSwiglu) {
+            const int j = r - BM, half = j / (BN / 2), jj = j % (BN / 2);
+            grow = half * n_out + min(n0 + jj, n_out - 1);
         } else {
-            ok = n0 + j < N;
-            wrow = n0 + j;
+            grow = min(n0 + r - BM, N - 1);
         }
-        b_ok[t] = ok;
-        b_ptr[t] = W + (size_t)(ok ? wrow : 0) * K + ld_kc * 8;
+        goff[t] = (uint32_t)grow * (uint32_t)K * 2u + kc * 16;
     }
-
-    uint4 a_reg[A_LOADS], b_reg[B_LOADS];
-    auto load_global = [&](int kt) {
-        const int k = kbeg + kt * kBK;
-        const bool kin = k + ld_kc * 8 < kend;
-#pragma unroll
-        for (int t = 0; t < A_LOADS; ++t)
-            a_reg[t] = (a_ok[t] && kin) ? *reinterpret_cast<const uint4 *>(a_ptr[t] + k) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-        for (int t = 0; t < B_LOADS; ++t)
-            b_reg[t] = (b_ok[t] && kin) ? *reinterpret_cast<const uint4 *>(b_ptr[t] + k) : make_uint4(0, 0, 0, 0);
-    };
-    auto store_lds = [&](int stage) {
-        uint4 *as = smem + stage * STAGE;
-        uint4 *bs = as + BM * kChunksPerRow;
-#pragma unroll
-        for (int t = 0; t < A_LOADS; ++t) {
-            const int row = ld_row + t * 32;
-            as[row * kChunksPerRow + (ld_kc ^ (row & 7))] = a_reg[t];
-        }
-#pragma unroll
-        for (int t = 0; t < B_LOADS; ++t) {
-            const int row = ld_row + t * 32;
-            bs[row * kChunksPerRow + (ld_kc ^ (row & 7))] = b_reg[t];
-        }
-    };
+    const char *Ab = reinterpret_cast<const char *>(A) + (size_t)kbeg * 2;
+    const char *Wb = reinterpret_cast<const char *>(W) + (size_t)kbeg * 2;
+#define DLLM_ISSUE_STAGE(kt_, stage_)                                                        \
+    do {                                                                                     \
+        const char *pa_ = Ab + (size_t)(kt_) * (kBK * 2), *pw_ = Wb + (size_t)(kt_) * (kBK * 2); \
+        const uint32_t dst_ = lds_addr_of(smem + (stage_) * STAGE + wave * 64);              \
+        _Pragma("unroll") for (int t = 0; t < LOADS; ++t)                                    \
+            async_load16(t < A_LOADS ? pa_ : pw_, goff[t], dst_ + t * 4096);                 \
+    } while (0)
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -138,109 +245,177 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint16_t *__restri
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    // LDS rows of this wave's fragments
     int a_row[TM], b_row[TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) a_row[i] = wm * WTM + i * 32 + l32;
+    for (int i = 0; i < TM; ++i) a_row[i] = (wm * WTM + i * 32 + l32) * kChunksPerRow;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        if (EPI == kEpiSwiglu) {
-            constexpr int HALF_TN = TN / 2 > 0 ? TN / 2 : 1;
-            b_row[j] = (j / HALF_TN) * (BN / 2) + wn * (WTN / 2) + (j % HALF_TN) * 32 + l32;
-        } else {
-            b_row[j] = wn * WTN + j * 32 + l32;
-        }
-    }
-    const int sw = l32 & 7;
+    for (int j = 0; j < TN; ++j) b_row[j] = w_frag_row<BM, BN, WTN, TN, EPI>(j, wn, l32) * kChunksPerRow;
+    const int sw = (l32 >> 1) & 7;
 
-    if (nk > 0) {
-        load_global(0);
-        store_lds(0);
-    }
-    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s)
+        if (s < nk) DLLM_ISSUE_STAGE(s, s);
 
     for (int kt = 0; kt < nk; ++kt) {
-        const bool more = kt + 1 < nk;
-        if (more) load_global(kt + 1);
-        const uint4 *as = smem + (kt & 1) * STAGE;
-        const uint4 *bs = as + BM * kChunksPerRow;
+        // step kt has landed once only the copies issued after it are outstanding
+        const int ahead = min(NST - 2, nk - 1 - kt);
+        if (NST >= 4 && ahead >= 2) wait_vmcnt<2 * LOADS>();
+        else if (NST >= 3 && ahead >= 1) wait_vmcnt<LOADS>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();  // also: every wave is done reading the stage refilled below
+        asm volatile("" ::: "memory");
+        if (kt + NST - 1 < nk) DLLM_ISSUE_STAGE(kt + NST - 1, (kt + NST - 1) % NST);
+        const uint4 *st = smem + (kt % NST) * STAGE;
+        bf16x8 af[2][TM], bfr[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[0][i] = as_bf16x8(st[a_row[i] + (lhalf ^ sw)]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[0][j] = as_bf16x8(st[b_row[j] + (lhalf ^ sw)]);
+#pragma unroll
+        for (int kk = 0; kk < kBK / 16; ++kk) {
+            const int cur = kk & 1, nxt = cur ^ 1;
+            if (kk + 1 < kBK / 16) {
+                const int ch = ((kk + 1) * 2 + lhalf) ^ sw;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) af[nxt][i] = as_bf16x8(st[a_row[i] + ch]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bfr[nxt][j] = as_bf16x8(st[b_row[j] + ch]);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // next fragments are requested before this substep's MFMAs
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#undef DLLM_ISSUE_STAGE
+    store_tile<TM, TN, WTM, WTN, EPI>(acc, Cout, M, N, n_out, m0, n0, wm, wn, l32, lhalf, blockIdx.y);
+}
+
+// ---- fallback kernel: any K % 8 == 0 -------------------------------------------
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ __launch_bounds__(kThreads) void gemm_reg_kernel(const uint16_t *__restrict__ A,
+                                                            const uint16_t *__restrict__ W, void *__restrict__ Cout,
+                                                            int M, int N, int K, int k_per_split, int num_m, int num_n)
+{
+    static_assert(WM * WN == 4, "4 waves per workgroup");
+    constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
+    static_assert(EPI != kEpiSwiglu || (TN % 2 == 0), "SwiGLU pairs gate/up sub-tiles");
+    constexpr int ROWS = BM + BN;
+    constexpr int LOADS = ROWS * kChunksPerRow / kThreads;
+    constexpr int A_LOADS = BM * kChunksPerRow / kThreads;
+    constexpr int STAGE = ROWS * kChunksPerRow;
+    extern __shared__ uint4 smem[];
+
+    int pid_m, pid_n;
+    tile_of(blockIdx.x, num_m, num_n, pid_m, pid_n);
+    constexpr int BN_OUT = (EPI == kEpiSwiglu) ? BN / 2 : BN;
+    const int m0 = pid_m * BM, n0 = pid_n * BN_OUT;
+    const int n_out = (EPI == kEpiSwiglu) ? N / 2 : N;
+    const int kbeg = blockIdx.y * k_per_split;
+    const int kend = min(K, kbeg + k_per_split);
+    const int nk = (kend - kbeg + kBK - 1) / kBK;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave / WN, wn = wave % WN;
+    const int l32 = lane & 31, lhalf = lane >> 5;
+
+    const int ld_row = tid >> 3, ld_kc = tid & 7;  // + 32 rows per extra load
+    const uint16_t *src[LOADS];
+    bool ok[LOADS];
+#pragma unroll
+    for (int t = 0; t < LOADS; ++t) {
+        const int r = ld_row + t * 32;
+        int grow;
+        if (t < A_LOADS) {
+            ok[t] = m0 + r < M;
+            grow = m0 + r;
+        } else if (EPI == kEpiSwiglu) {
+            const int j = r - BM, half = j / (BN / 2), jj = j % (BN / 2);
+            ok[t] = n0 + jj < n_out;
+            grow = half * n_out + n0 + jj;
+        } else {
+            ok[t] = n0 + r - BM < N;
+            grow = n0 + r - BM;
+        }
+        src[t] = (t < A_LOADS ? A : W) + (size_t)(ok[t] ? grow : 0) * K + ld_kc * 8;
+    }
+    uint4 reg[LOADS];
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    int a_row[TM], b_row[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a_row[i] = (wm * WTM + i * 32 + l32) * kChunksPerRow;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b_row[j] = w_frag_row<BM, BN, WTN, TN, EPI>(j, wn, l32) * kChunksPerRow;
+    const int sw = (l32 >> 1) & 7;
+
+    for (int kt = 0; kt <= nk; ++kt) {
+        // registers of step kt-1 go to LDS, step kt is fetched, step kt-1 is multiplied
+        if (kt > 0) {
+            uint4 *dst = smem + ((kt - 1) & 1) * STAGE;
+#pragma unroll
+            for (int t = 0; t < LOADS; ++t) {
+                const int r = ld_row + t * 32;
+                dst[r * kChunksPerRow + (ld_kc ^ ((r >> 1) & 7))] = reg[t];
+            }
+        }
+        if (kt < nk) {
+            const int k = kbeg + kt * kBK;
+            const bool kin = k + ld_kc * 8 < kend;
+#pragma unroll
+            for (int t = 0; t < LOADS; ++t)
+                reg[t] = (ok[t] && kin) ? *reinterpret_cast<const uint4 *>(src[t] + k) : make_uint4(0, 0, 0, 0);
+        }
+        __syncthreads();
+        if (kt == 0) continue;
+        const uint4 *st = smem + ((kt - 1) & 1) * STAGE;
 #pragma unroll
         for (int kk = 0; kk < kBK / 16; ++kk) {
             const int ch = (kk * 2 + lhalf) ^ sw;
             bf16x8 af[TM], bfr[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = as_bf16x8(as[a_row[i] * kChunksPerRow + ch]);
+            for (int i = 0; i < TM; ++i) af[i] = as_bf16x8(st[a_row[i] + ch]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bfr[j] = as_bf16x8(bs[b_row[j] * kChunksPerRow + ch]);
+            for (int j = 0; j < TN; ++j) bfr[j] = as_bf16x8(st[b_row[j] + ch]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
-        if (more) store_lds((kt + 1) & 1);
-        __syncthreads();
     }
-
-    // ---- epilogue -----------------------------------------------------------
-    // accumulator element e of lane l sits at row 8*(e/4) + 4*(l/32) + e%4, column l%32
-    if (EPI == kEpiBf16) {
-        uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + wn * WTN + j * 32 + l32;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = m0 + wm * WTM + i * 32 + 8 * (e / 4) + 4 * lhalf + (e % 4);
-                    if (row < M && col < N) C[(size_t)row * N + col] = float_to_bf16_bits(acc[i][j][e]);
-                }
-            }
-    } else if (EPI == kEpiSwiglu) {
-        uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
-        constexpr int HALF_TN = TN / 2 > 0 ? TN / 2 : 1;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < HALF_TN; ++j) {
-                const int col = n0 + wn * (WTN / 2) + j * 32 + l32;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = m0 + wm * WTM + i * 32 + 8 * (e / 4) + 4 * lhalf + (e % 4);
-                    const float g = acc[i][j][e], u = acc[i][j + HALF_TN][e];
-                    const float y = g / (1.0f + __expf(-g)) * u;
-                    if (row < M && col < n_out) C[(size_t)row * n_out + col] = float_to_bf16_bits(y);
-                }
-            }
-    } else {
-        float *C = reinterpret_cast<float *>(Cout) + (size_t)blockIdx.y * M * N;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + wn * WTN + j * 32 + l32;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = m0 + wm * WTM + i * 32 + 8 * (e / 4) + 4 * lhalf + (e % 4);
-                    if (row < M && col < N) C[(size_t)row * N + col] = acc[i][j][e];
-                }
-            }
-    }
+    store_tile<TM, TN, WTM, WTN, EPI>(acc, Cout, M, N, n_out, m0, n0, wm, wn, l32, lhalf, blockIdx.y);
 }
 
 // ---- host side ----------------------------------------------------------------
 
+// Tile shapes with the cost of one K-step and of the epilogue in shader clocks,
+// measured on MI355X at M = 512 (copy and math of a step overlap only partly:
+// the LDS port is shared by the asynchronous copies and the fragment reads).
 struct TileCfg {
-    int bm, bn;
-    float eff;  // relative MFMA efficiency of the tile shape (bigger tiles reuse more)
+    int bm, bn, nst;
+    float step_clk, epi_clk;
 };
-constexpr int kNumCfg = 4;
-const TileCfg kCfg[kNumCfg] = {{256, 256, 1.00f}, {256, 128, 0.85f}, {128, 128, 0.65f}, {128, 64, 0.40f}};
+constexpr int kNumCfg = 6;
+const TileCfg kCfg[kNumCfg] = {
+    {256, 256, 2, 3580.f, 24000.f}, {256, 192, 2, 2870.f, 18000.f}, {256, 128, 3, 2120.f, 11800.f},
+    {256, 96, 3, 1950.f, 8900.f},   {128, 128, 3, 1300.f, 5800.f},  {128, 64, 4, 800.f, 3000.f},
+};
 constexpr int kNumCU = 256;
+constexpr int kLdsPerCU = 160 * 1024;
 
 struct Plan {
     int cfg, splits;
+    bool fast;  // gemm_dl_kernel
 };
 
 int env_int(const char *name, int dflt)
@@ -249,54 +424,80 @@ int env_int(const char *name, int dflt)
     return s ? atoi(s) : dflt;
 }
 
-// Pick the tile shape (and K splits for the partial-sum epilogue) with the
-// lowest modelled time: full waves of workgroups over 256 CUs, weighted by the
-// tile's efficiency, plus the traffic of the fp32 slabs.
+bool cfg_allows(int c, GemmEpilogue epi, bool fast)
+{
+    if (epi == kEpiSwiglu && c == 3) return false;   // 256x96 as 4x1 waves: odd number of sub-tiles per wave
+    if (epi == kEpiPartial && c == 0) return false;  // 256x256 fp32 epilogue runs out of registers
+    if (!fast && c < 2) return false;                // the register-staged kernel keeps to the smaller tiles
+    return true;
+}
+
+// Lowest modelled time: rounds of workgroups over the CUs, each round costing
+// the K-steps of one tile plus its epilogue, plus the traffic of the fp32 slabs.
 Plan make_plan(GemmEpilogue epi, int M, int N, int K)
 {
     const int n_out = epi == kEpiSwiglu ? N / 2 : N;
-    Plan best{2, 1};
+    // the asynchronous-copy kernel needs whole K-steps and 32-bit byte offsets
+    const bool fast = (K % kBK == 0) && ((double)M * K * 2 < 4.0e9) && ((double)N * K * 2 < 4.0e9) &&
+                      env_int("DLLM_GEMM_FALLBACK", 0) == 0;
+    const int fc = env_int("DLLM_GEMM_CFG", -1), fs = env_int("DLLM_GEMM_SPLITS", -1);
+    Plan best{4, 1, fast};
     double best_cost = 1e300;
     const int max_splits = epi == kEpiPartial ? 8 : 1;
     for (int c = 0; c < kNumCfg; ++c) {
-        const int bn_out = epi == kEpiSwiglu ? kCfg[c].bn / 2 : kCfg[c].bn;
-        const long tiles = (long)((M + kCfg[c].bm - 1) / kCfg[c].bm) * ((n_out + bn_out - 1) / bn_out);
-        const int per_cu = (kCfg[c].bm + kCfg[c].bn) * 128 * 2 <= 80 * 1024 ? 2 : 1;  // LDS-limited residency
-        for (int s = 1; s <= max_splits; s *= 2) {
+        if (!cfg_allows(c, epi, fast) || (fc >= 0 && fc < kNumCfg && cfg_allows(fc, epi, fast) && c != fc)) continue;
+        const TileCfg &t = kCfg[c];
+        const int bn_out = epi == kEpiSwiglu ? t.bn / 2 : t.bn;
+        const long tiles = (long)((M + t.bm - 1) / t.bm) * ((n_out + bn_out - 1) / bn_out);
+        const int per_cu = kLdsPerCU / ((fast ? t.nst : 2) * (t.bm + t.bn) * 128) >= 2 ? 2 : 1;
+        for (int s = 1; s <= max_splits; ++s) {
+            if (fs >= 1 && fs <= max_splits && s != fs) continue;
             const int kps = ((K + s - 1) / s + kBK - 1) / kBK * kBK;
-            if (s > 1 && kps * (s - 1) >= K) continue;
+            if (s > 1 && (long)kps * (s - 1) >= K) continue;   // the last split would be empty
             const long wgs = tiles * s;
-            const long waves = (wgs + (long)kNumCU * per_cu - 1) / ((long)kNumCU * per_cu);
-            double cost = (double)waves * per_cu * kCfg[c].bm * kCfg[c].bn * (double)kps / kCfg[c].eff;
-            cost += 4000.0 * kBK * 64;                                  // prologue / epilogue per launch
-            if (epi == kEpiPartial) cost += (double)s * M * N * 40.0;   // slab write + read
-            if (cost < best_cost) { best_cost = cost; best = Plan{c, s}; }
+            const long rounds = (wgs + (long)kNumCU * per_cu - 1) / ((long)kNumCU * per_cu);
+            double cost = (double)rounds * per_cu * ((double)(kps / kBK) * t.step_clk + t.epi_clk + 2500.0);
+            if (epi == kEpiPartial) cost += (double)s * M * N * 8.0 / (4000.0 / 2.4);  // slab write + read, ~4 TB/s
+            if (cost < best_cost) { best_cost = cost; best = Plan{c, s, fast}; }
         }
     }
-    const int fc = env_int("DLLM_GEMM_CFG", -1), fs = env_int("DLLM_GEMM_SPLITS", -1);
-    if (fc >= 0 && fc < kNumCfg) best.cfg = fc;
-    if (fs >= 1 && epi == kEpiPartial) best.splits = fs;
     return best;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
-hipError_t launch_cfg(hipStream_t stream, const void *A, const void *W, void *C, int M, int N, int K, int splits)
+template <int BM, int BN, int WM, int WN, int NST, int EPI>
+hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *W, void *C, int M, int N, int K,
+                      int splits)
 {
     constexpr int BN_OUT = EPI == kEpiSwiglu ? BN / 2 : BN;
     const int n_out = EPI == kEpiSwiglu ? N / 2 : N;
     const int num_m = (M + BM - 1) / BM, num_n = (n_out + BN_OUT - 1) / BN_OUT;
     const int kps = ((K + splits - 1) / splits + kBK - 1) / kBK * kBK;
-    const size_t lds = (size_t)2 * (BM + BN) * kChunksPerRow * sizeof(uint4);
-    auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
+    const dim3 grid(num_m * num_n, splits), block(kThreads);
+    if (fast) {
+        const size_t lds = (size_t)NST * (BM + BN) * kChunksPerRow * sizeof(uint4);
+        auto kern = gemm_dl_kernel<BM, BN, WM, WN, NST, EPI>;
+        static bool attr_done = false;
+        if (!attr_done) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, (const uint16_t *)A, (const uint16_t *)W, C, M, N, K, kps,
+                           num_m, num_n);
+    } else {
+        const size_t lds = (size_t)2 * (BM + BN) * kChunksPerRow * sizeof(uint4);
+        auto kern = gemm_reg_kernel<BM, BN, WM, WN, EPI>;
+        static bool attr_done = false;
+        if (!attr_done) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, (const uint16_t *)A, (const uint16_t *)W, C, M, N, K, kps,
+                           num_m, num_n);
     }
-    hipLaunchKernelGGL(kern, dim3(num_m * num_n, splits), dim3(kThreads), lds, stream, (const uint16_t *)A,
-                       (const uint16_t *)W, C, M, N, K, kps, num_m, num_n);
     return hipGetLastError();
 }
 
@@ -304,10 +505,14 @@ template <int EPI>
 hipError_t dispatch(hipStream_t stream, Plan p, const void *A, const void *W, void *C, int M, int N, int K)
 {
     switch (p.cfg) {
-    case 0: return launch_cfg<256, 256, 2, 2, EPI>(stream, A, W, C, M, N, K, p.splits);
-    case 1: return launch_cfg<256, 128, 2, 2, EPI>(stream, A, W, C, M, N, K, p.splits);
-    case 2: return launch_cfg<128, 128, 2, 2, EPI>(stream, A, W, C, M, N, K, p.splits);
-    default: return launch_cfg<128, 64, 4, 1, EPI>(stream, A, W, C, M, N, K, p.splits);
+    case 0: return launch_cfg<256, 256, 2, 2, 2, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
+    case 1: return launch_cfg<256, 192, 4, 1, 2, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
+    case 2: return launch_cfg<256, 128, 2, 2, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
+    case 3:
+        if constexpr (EPI != kEpiSwiglu) return launch_cfg<256, 96, 4, 1, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
+        return hipErrorInvalidValue;
+    case 4: return launch_cfg<128, 128, 2, 2, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
+    default: return launch_cfg<128, 64, 4, 1, 4, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
     }
 }
 

@@ -58,11 +58,16 @@ GEMM_SHAPES = [  # M, N, K
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3])
-def test_linear(M, N, K, tile, monkeypatch):
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("fallback", [0, 1])
+def test_linear(M, N, K, tile, fallback, monkeypatch):
+    """Every tile shape, through the asynchronous-copy kernel (K % 64 == 0) and
+    through the register-staged kernel (forced, or picked for a ragged K)."""
     b = binding()
     if tile >= 0:
         monkeypatch.setenv("DLLM_GEMM_CFG", str(tile))
+    if fallback:
+        monkeypatch.setenv("DLLM_GEMM_FALLBACK", "1")
     A = rand_bf16((M, K), 1.0, 11, f"A{M}{K}")
     W = rand_bf16((N, K), 0.05, 12, f"W{N}{K}")
     got = f64(b.op_linear(A.to(DEV), W.to(DEV)))
@@ -71,11 +76,14 @@ def test_linear(M, N, K, tile, monkeypatch):
 
 
 @pytest.mark.parametrize("M,f,K", [(96, 688, 256), (130, 200, 128), (512, 1408, 512)])
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3])
-def test_linear_swiglu(M, f, K, tile, monkeypatch):
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 4, 5])
+@pytest.mark.parametrize("fallback", [0, 1])
+def test_linear_swiglu(M, f, K, tile, fallback, monkeypatch):
     b = binding()
     if tile >= 0:
         monkeypatch.setenv("DLLM_GEMM_CFG", str(tile))
+    if fallback:
+        monkeypatch.setenv("DLLM_GEMM_FALLBACK", "1")
     A = rand_bf16((M, K), 1.0, 21, f"A{M}{K}")
     W = rand_bf16((2 * f, K), 0.08, 22, f"W{f}{K}")
     got = f64(b.op_linear_swiglu(A.to(DEV), W.to(DEV)))
