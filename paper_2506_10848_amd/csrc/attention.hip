@@ -1,26 +1,34 @@
 // Non-causal flash-style attention for gfx950 (every query attends to all L
 // keys of its sequence; no mask).
 //
-// A wave owns 32 queries and walks the keys in tiles of 64.  Both products run
-// on the 32x32x16 bf16 MFMA with the queries on the lane axis:
+// A workgroup has 4 waves of 32 queries each.  With KVSPLIT = 1 they cover 128
+// queries and walk all keys together (64 keys per step).  With KVSPLIT = 2 (short
+// sequences, few workgroups) waves 0/1 and 2/3 form two halves that walk disjoint
+// halves of the key range for the same 64 queries and are merged at the end with
+// the log-sum-exp rule, which halves the length of the sequential chain.  Inside a wave (32
+// queries) both products run on the 32x32x16 bf16 MFMA with the queries on the
+// lane axis:
 //     S^T = K Q^T          (A = K rows from LDS,  B = Q kept in registers)
 //     O^T = V^T P^T        (A = V^T rows from LDS, B = P straight from the S^T
 //                           accumulators, no data movement)
 // so the running max, the running sum and the rescale factor of a query live in
-// the lane that owns it (the two lanes l and l+32 share a query and split the
-// keys).  The K index of the second product is a fixed permutation of the keys
-// that makes the S^T accumulator layout directly usable as the B operand; the
-// V^T fragment is read with the same permutation.  V is transposed on its way
-// into LDS.  Softmax runs in fp32 in the exp2 domain.
+// the lane that owns it (lanes l and l+32 share a query and split the keys).
+// The K index of the second product is a fixed permutation of the keys that
+// makes the S^T accumulator layout directly usable as the B operand; the V^T
+// fragment is read with the same permutation.  V is transposed on its way into
+// LDS.  The K / V tile of step t+1 is fetched into registers before the math of
+// step t, so the global-memory latency hides behind the MFMAs.  Softmax runs in
+// fp32 in the exp2 domain.
 #include "internal.h"
 
 namespace dllm {
 
 namespace {
 
-constexpr int kKeysPerTile = 64;
-constexpr int kVtStride = kKeysPerTile + 4;  // bf16 elements; 136-byte rows keep 8-byte reads conflict-free
+constexpr int kKeys = 64;           // keys per step
+constexpr int kVtStride = kKeys + 4;  // bf16 elements; 136-byte rows keep the 8-byte fragment reads conflict-free
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kThreads = 256;
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v)
 {
@@ -29,25 +37,52 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v)
     return c.b;
 }
 
-template <int DH, int NWAVES>
-__global__ __launch_bounds__(NWAVES * 64) void attention_kernel(const uint16_t *__restrict__ qkv,
-                                                                uint16_t *__restrict__ out, int L, int H)
+template <int DH, int KVSPLIT>
+struct Smem {
+    static constexpr int CH = DH / 8;  // 16-byte chunks per K row
+    uint4 Ks[KVSPLIT][kKeys * CH];
+    uint16_t Vt[KVSPLIT][DH * kVtStride];
+};
+
+// chunk swizzle of a K row: rows of 256 bytes cover all 64 banks, rows of 128
+// bytes cover half of them
+template <int DH>
+__device__ __forceinline__ int k_swz(int row)
 {
-    constexpr int NT = NWAVES * 64;
-    constexpr int KSTEPS = DH / 16;       // MFMA K steps over the head dimension
-    constexpr int DSUB = DH / 32;         // 32-row sub-tiles of O^T
-    constexpr int CH = DH / 8;            // 16-byte chunks per K row
-    __shared__ uint4 Ks[kKeysPerTile * CH];
-    __shared__ __attribute__((aligned(16))) uint16_t Vt[DH * kVtStride];
+    return DH == 128 ? (row & 15) : ((row >> 1) & 7);
+}
+
+template <int DH, int KVSPLIT>
+__global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__restrict__ qkv,
+                                                             uint16_t *__restrict__ out, int L, int H)
+{
+    constexpr int KSTEPS = DH / 16;  // MFMA K steps over the head dimension
+    constexpr int DSUB = DH / 32;    // 32-row sub-tiles of O^T
+    constexpr int CH = DH / 8;
+    constexpr int HT = kThreads / KVSPLIT;             // threads that share one K / V tile
+    constexpr int QT = 128 / KVSPLIT;                  // queries per workgroup
+    constexpr int K_LOADS = kKeys * CH / HT;           // per thread
+    constexpr int V_TOTAL = (kKeys / 4) * CH;          // 4-key x 8-dim blocks of a V tile
+    constexpr int V_BLOCKS = (V_TOTAL + HT - 1) / HT;  // per thread
+    extern __shared__ uint4 smem_raw[];
+    Smem<DH, KVSPLIT> &sm = *reinterpret_cast<Smem<DH, KVSPLIT> *>(smem_raw);
 
     const int d = H * DH;
     const size_t ld = (size_t)3 * d;
     const int h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int half = KVSPLIT == 2 ? wave >> 1 : 0, qgroup = KVSPLIT == 2 ? wave & 1 : wave, htid = tid & (HT - 1);
     const int l32 = lane & 31, g = lane >> 5;
-    const int q0 = blockIdx.x * (NWAVES * 32) + wave * 32;
+    const int q0 = blockIdx.x * QT + qgroup * 32;
     const uint16_t *base = qkv + (size_t)b * L * ld;
     const float c = kLog2e / sqrtf((float)DH);
+
+    // key steps of this half
+    const int ntiles = (L + kKeys - 1) / kKeys;
+    const int n_first = KVSPLIT == 2 ? (ntiles + 1) / 2 : ntiles;
+    const int my_first = half ? n_first : 0;
+    const int my_count = half ? ntiles - n_first : n_first;
+    const int iters = n_first;  // both halves loop together
 
     // Q fragments (B operand): lane (query l32, half g) holds dims t*16 + g*8 .. +8
     bf16x8 qf[KSTEPS];
@@ -58,40 +93,47 @@ __global__ __launch_bounds__(NWAVES * 64) void attention_kernel(const uint16_t *
         for (int t = 0; t < KSTEPS; ++t) qf[t] = as_bf16x8(*reinterpret_cast<const uint4 *>(qp + t * 16));
     }
 
-    floatx16 o[DSUB];
-#pragma unroll
-    for (int i = 0; i < DSUB; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[i][e] = 0.0f;
-    float m_run = -3.0e38f, l_run = 0.0f;
-
     const uint16_t *kbase = base + d + (size_t)h * DH;
     const uint16_t *vbase = base + 2 * d + (size_t)h * DH;
+    uint4 kreg[K_LOADS], vreg[V_BLOCKS][4];
 
-    for (int key0 = 0; key0 < L; key0 += kKeysPerTile) {
-        __syncthreads();  // previous tile fully consumed
-        // K tile: 64 rows x CH chunks, swizzled by row
-        for (int idx = tid; idx < kKeysPerTile * CH; idx += NT) {
-            const int row = idx / CH, ch = idx % CH;
+    auto fetch = [&](int it) {  // step `it` of this half -> registers (zeros past the end)
+        const int key0 = (my_first + it) * kKeys;
+        const bool live = it < my_count;
+#pragma unroll
+        for (int t = 0; t < K_LOADS; ++t) {
+            const int idx = htid + t * HT, row = idx / CH, ch = idx % CH;
             const int key = key0 + row;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (key < L) v = *reinterpret_cast<const uint4 *>(kbase + (size_t)key * ld + ch * 8);
-            Ks[row * CH + (ch ^ (row & 7))] = v;
+            kreg[t] = (live && key < L) ? *reinterpret_cast<const uint4 *>(kbase + (size_t)key * ld + ch * 8)
+                                        : make_uint4(0, 0, 0, 0);
         }
-        // V tile, transposed: a thread moves a 4-key x 8-dim block
-        for (int blk = tid; blk < (kKeysPerTile / 4) * CH; blk += NT) {
-            const int kg = blk % (kKeysPerTile / 4), dg = blk / (kKeysPerTile / 4);
-            uint4 v[4];
+#pragma unroll
+        for (int t = 0; t < V_BLOCKS; ++t) {
+            const int blk = htid + t * HT, kg = blk % (kKeys / 4), dg = blk / (kKeys / 4);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int key = key0 + kg * 4 + r;
-                v[r] = make_uint4(0, 0, 0, 0);
-                if (key < L) v[r] = *reinterpret_cast<const uint4 *>(vbase + (size_t)key * ld + dg * 8);
+                vreg[t][r] = (live && key < L && blk < V_TOTAL) ? *reinterpret_cast<const uint4 *>(vbase + (size_t)key * ld + dg * 8)
+                                               : make_uint4(0, 0, 0, 0);
             }
-            const uint32_t *w0 = reinterpret_cast<const uint32_t *>(&v[0]);
-            const uint32_t *w1 = reinterpret_cast<const uint32_t *>(&v[1]);
-            const uint32_t *w2 = reinterpret_cast<const uint32_t *>(&v[2]);
-            const uint32_t *w3 = reinterpret_cast<const uint32_t *>(&v[3]);
+        }
+    };
+    auto stash = [&]() {  // registers -> LDS of this half: K swizzled, V transposed
+        uint4 *Ks = sm.Ks[half];
+        uint16_t *Vt = sm.Vt[half];
+#pragma unroll
+        for (int t = 0; t < K_LOADS; ++t) {
+            const int idx = htid + t * HT, row = idx / CH, ch = idx % CH;
+            Ks[row * CH + (ch ^ k_swz<DH>(row))] = kreg[t];
+        }
+#pragma unroll
+        for (int t = 0; t < V_BLOCKS; ++t) {
+            const int blk = htid + t * HT, kg = blk % (kKeys / 4), dg = blk / (kKeys / 4);
+            if (blk >= V_TOTAL) continue;
+            const uint32_t *w0 = reinterpret_cast<const uint32_t *>(&vreg[t][0]);
+            const uint32_t *w1 = reinterpret_cast<const uint32_t *>(&vreg[t][1]);
+            const uint32_t *w2 = reinterpret_cast<const uint32_t *>(&vreg[t][2]);
+            const uint32_t *w3 = reinterpret_cast<const uint32_t *>(&vreg[t][3]);
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 // dims 2p (low halves) and 2p+1 (high halves) of the four keys
@@ -104,81 +146,124 @@ __global__ __launch_bounds__(NWAVES * 64) void attention_kernel(const uint16_t *
                 *reinterpret_cast<uint2 *>(&Vt[(dg * 8 + 2 * p + 1) * kVtStride + kg * 4]) = hi;
             }
         }
-        __syncthreads();
+    };
 
-        // S^T for two 32-key sub-tiles
-        floatx16 s[2];
+    floatx16 o[DSUB];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
+    for (int i = 0; i < DSUB; ++i)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) s[sub][e] = 0.0f;
-            const int row = sub * 32 + l32;
+        for (int e = 0; e < 16; ++e) o[i][e] = 0.0f;
+    float m_run = -3.0e38f, l_run = 0.0f;
+
+    fetch(0);
+    stash();
+    __syncthreads();
+
+    for (int it = 0; it < iters; ++it) {
+        if (it + 1 < iters) fetch(it + 1);
+        if (it < my_count) {
+            const int key0 = (my_first + it) * kKeys;
+            const uint4 *Ks = sm.Ks[half];
+            const uint16_t *Vt = sm.Vt[half];
+            // S^T for two 32-key sub-tiles
+            floatx16 s[2];
 #pragma unroll
-            for (int t = 0; t < KSTEPS; ++t) {
-                const bf16x8 kf = as_bf16x8(Ks[row * CH + ((t * 2 + g) ^ (row & 7))]);
-                s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s[sub], 0, 0, 0);
+            for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) s[sub][e] = 0.0f;
+                const int row = sub * 32 + l32;
+                const int swz = k_swz<DH>(row);
+#pragma unroll
+                for (int t = 0; t < KSTEPS; ++t) {
+                    const bf16x8 kf = as_bf16x8(Ks[row * CH + ((t * 2 + g) ^ swz)]);
+                    s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s[sub], 0, 0, 0);
+                }
             }
-        }
-        // keys past the end of the sequence do not exist
-        if (key0 + kKeysPerTile > L) {
+            // keys past the end of the sequence do not exist
+            if (key0 + kKeys > L) {
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int key = key0 + sub * 32 + 8 * (e / 4) + 4 * g + (e % 4);
+                        if (key >= L) s[sub][e] = -INFINITY;
+                    }
+            }
+            // online softmax for this lane's query
+            float mt = s[0][0];
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mt = fmaxf(mt, s[sub][e]);
+            mt = fmaxf(mt, __shfl_xor(mt, 32, kWave));
+            const float m_new = fmaxf(m_run, mt);
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+            const float off = -m_new * c;
+            float psum = 0.0f;
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int key = key0 + sub * 32 + 8 * (e / 4) + 4 * g + (e % 4);
-                    if (key >= L) s[sub][e] = -INFINITY;
+                    const float p = __builtin_amdgcn_exp2f(fmaf(s[sub][e], c, off));
+                    s[sub][e] = p;
+                    psum += p;
+                }
+            l_run = l_run * alpha + psum;
+            m_run = m_new;
+#pragma unroll
+            for (int i = 0; i < DSUB; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
+
+            // O^T += V^T P^T, 16 keys per MFMA
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    union { uint4 u; bf16x8 v; } pf;
+                    pf.u.x = pack_bf16x2(s[sub][kb * 8 + 0], s[sub][kb * 8 + 1]);
+                    pf.u.y = pack_bf16x2(s[sub][kb * 8 + 2], s[sub][kb * 8 + 3]);
+                    pf.u.z = pack_bf16x2(s[sub][kb * 8 + 4], s[sub][kb * 8 + 5]);
+                    pf.u.w = pack_bf16x2(s[sub][kb * 8 + 6], s[sub][kb * 8 + 7]);
+                    const int kcol = sub * 32 + kb * 16 + 4 * g;  // keys kcol..+3 and kcol+8..+11
+#pragma unroll
+                    for (int i = 0; i < DSUB; ++i) {
+                        const uint16_t *vr = &Vt[(i * 32 + l32) * kVtStride + kcol];
+                        union { uint2 h2[2]; bf16x8 v; } vf;
+                        vf.h2[0] = *reinterpret_cast<const uint2 *>(vr);
+                        vf.h2[1] = *reinterpret_cast<const uint2 *>(vr + 8);
+                        o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[i], 0, 0, 0);
+                    }
                 }
         }
-        // online softmax for this lane's query
-        float mt = s[0][0];
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) mt = fmaxf(mt, s[sub][e]);
-        mt = fmaxf(mt, __shfl_xor(mt, 32, kWave));
-        const float m_new = fmaxf(m_run, mt);
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-        const float off = -m_new * c;
-        float psum = 0.0f;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[sub][e], c, off));
-                s[sub][e] = p;
-                psum += p;
-            }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-#pragma unroll
-        for (int i = 0; i < DSUB; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
-
-        // O^T += V^T P^T, 16 keys per MFMA
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                union { uint4 u; bf16x8 v; } pf;
-                pf.u.x = pack_bf16x2(s[sub][kb * 8 + 0], s[sub][kb * 8 + 1]);
-                pf.u.y = pack_bf16x2(s[sub][kb * 8 + 2], s[sub][kb * 8 + 3]);
-                pf.u.z = pack_bf16x2(s[sub][kb * 8 + 4], s[sub][kb * 8 + 5]);
-                pf.u.w = pack_bf16x2(s[sub][kb * 8 + 6], s[sub][kb * 8 + 7]);
-                const int kcol = sub * 32 + kb * 16 + 4 * g;  // keys kcol..+3 and kcol+8..+11
-#pragma unroll
-                for (int i = 0; i < DSUB; ++i) {
-                    const uint16_t *vr = &Vt[(i * 32 + l32) * kVtStride + kcol];
-                    union { uint2 h[2]; bf16x8 v; } vf;
-                    vf.h[0] = *reinterpret_cast<const uint2 *>(vr);
-                    vf.h[1] = *reinterpret_cast<const uint2 *>(vr + 8);
-                    o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[i], 0, 0, 0);
-                }
-            }
+        __syncthreads();  // everyone is done with this step's tiles
+        if (it + 1 < iters) stash();
+        __syncthreads();
     }
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
-    const float inv = 1.0f / l_tot;
+    // ---- merge the two halves (log-sum-exp), normalise, store ----------------
+    float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+    float a0 = 1.0f, a1 = 0.0f, l1 = 0.0f;
+    float *xo = reinterpret_cast<float *>(smem_raw);       // [qgroup][DSUB*16][64 lanes]
+    float *xs = xo + 2 * DSUB * 16 * 64;                    // [qgroup][2][64 lanes]: m, l
+    if (KVSPLIT == 2) {
+        if (half == 1) {
+#pragma unroll
+            for (int i = 0; i < DSUB; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) xo[(qgroup * DSUB * 16 + i * 16 + e) * 64 + lane] = o[i][e];
+            xs[(qgroup * 2 + 0) * 64 + lane] = m_run;
+            xs[(qgroup * 2 + 1) * 64 + lane] = l_tot;
+        }
+        __syncthreads();
+        if (half == 1) return;
+        const float m1 = xs[(qgroup * 2 + 0) * 64 + lane];
+        l1 = xs[(qgroup * 2 + 1) * 64 + lane];
+        const float m = fmaxf(m_run, m1);
+        a0 = __builtin_amdgcn_exp2f((m_run - m) * c);
+        a1 = __builtin_amdgcn_exp2f((m1 - m) * c);
+    }
+    const float inv = 1.0f / (l_tot * a0 + l1 * a1);
     const int q = q0 + l32;
     if (q < L) {
         uint16_t *op = out + ((size_t)b * L + q) * d + (size_t)h * DH;
@@ -186,28 +271,49 @@ __global__ __launch_bounds__(NWAVES * 64) void attention_kernel(const uint16_t *
         for (int i = 0; i < DSUB; ++i)
 #pragma unroll
             for (int e4 = 0; e4 < 4; ++e4) {
+                float y[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float v = o[i][e4 * 4 + e] * a0;
+                    if (KVSPLIT == 2) v += xo[(qgroup * DSUB * 16 + i * 16 + e4 * 4 + e) * 64 + lane] * a1;
+                    y[e] = v * inv;
+                }
                 const int dim = i * 32 + 8 * e4 + 4 * g;
                 uint2 w;
-                w.x = pack_bf16x2(o[i][e4 * 4 + 0] * inv, o[i][e4 * 4 + 1] * inv);
-                w.y = pack_bf16x2(o[i][e4 * 4 + 2] * inv, o[i][e4 * 4 + 3] * inv);
+                w.x = pack_bf16x2(y[0], y[1]);
+                w.y = pack_bf16x2(y[2], y[3]);
                 *reinterpret_cast<uint2 *>(op + dim) = w;
             }
     }
 }
 
+template <int DH, int KVSPLIT>
+hipError_t launch_split(hipStream_t stream, const void *qkv, void *out, int B, int L, int H)
+{
+    constexpr int QT = 128 / KVSPLIT;
+    const size_t lds = sizeof(Smem<DH, KVSPLIT>);
+    static_assert(KVSPLIT == 1 || sizeof(Smem<DH, 2>) >= (2 * (DH / 32) * 16 * 64 + 4 * 64) * sizeof(float),
+                  "merge buffer fits");
+    auto kern = attention_kernel<DH, KVSPLIT>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((L + QT - 1) / QT, H, B), dim3(kThreads), lds, stream, (const uint16_t *)qkv,
+                       (uint16_t *)out, L, H);
+    return hipGetLastError();
+}
+
 template <int DH>
 hipError_t launch_dh(hipStream_t stream, const void *qkv, void *out, int B, int L, int H)
 {
-    // 4 waves (128 queries) per workgroup when that still fills the chip, else 2
-    const long wg4 = (long)((L + 127) / 128) * H * B;
-    if (wg4 >= 512) {
-        hipLaunchKernelGGL((attention_kernel<DH, 4>), dim3((L + 127) / 128, H, B), dim3(256), 0, stream,
-                           (const uint16_t *)qkv, (uint16_t *)out, L, H);
-    } else {
-        hipLaunchKernelGGL((attention_kernel<DH, 2>), dim3((L + 63) / 64, H, B), dim3(128), 0, stream,
-                           (const uint16_t *)qkv, (uint16_t *)out, L, H);
-    }
-    return hipGetLastError();
+    // few workgroups: split the keys inside a workgroup to shorten the chain
+    const long wgs128 = (long)((L + 127) / 128) * H * B;
+    if (wgs128 < 1024) return launch_split<DH, 2>(stream, qkv, out, B, L, H);
+    return launch_split<DH, 1>(stream, qkv, out, B, L, H);
 }
 
 }  // namespace
