@@ -24,11 +24,12 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0              # MI355X HBM3E
 
 
-def step_flops(cfg, B, L):
-    """Algorithmic flops of one forward: GEMMs 2*M*(nL*(4d^2 + 3df) + dV) plus attention 4*nL*B*L^2*d."""
+def step_flops(cfg, B, L, vocab_rows):
+    """Executed flops of one step: layer GEMMs 2*M*nL*(4d^2 + 3df), attention 4*nL*B*L^2*d, and the
+    vocabulary projection 2*rows*d*V over the rows the selector reads (the windows)."""
     d, f, V, nl = cfg["d_model"], cfg["d_ffn"], cfg["vocab"], cfg["n_layers"]
     M = B * L
-    return 2.0 * M * (nl * (4 * d * d + 3 * d * f) + d * V) + 4.0 * nl * B * L * L * d
+    return 2.0 * M * nl * (4 * d * d + 3 * d * f) + 2.0 * vocab_rows * d * V + 4.0 * nl * B * L * L * d
 
 
 def to_bits(t):
@@ -151,7 +152,7 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     assert int(mask.sum()) == B * G - B * (args.steps + args.warmup), "every step must commit one token per sequence"
 
-    flops = step_flops(mc, B, L)
+    flops = step_flops(mc, B, L, vocab_rows=B * G)          # slow-stage window = the whole generated region
     k_flops = 2.0 * B * L * mc["d_model"] * 2 * mc["d_ffn"]          # one gate/up GEMM launch
     k_avg_ms = k_ms / max(k_launches, 1)
     achieved = k_flops / (k_avg_ms * 1e-3) / 1e12

@@ -173,7 +173,9 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
                 const dllm_decode_params *p, int32_t *steps_taken, dllm_step_stat *stats, int32_t stats_capacity);
 
 /* Test and measurement hooks: device pointers into the workspace, valid until
- * the next call on the handle.  logits: bf16 [B*L][vocab] of the last forward;
+ * the next call on the handle.  logits: bf16 [B*L][vocab] of the last forward
+ * (after dllm_step only the rows inside each sequence's window are defined:
+ * the vocabulary projection skips rows the selector does not read);
  * pred / conf: int32 / float [B*L] of the last row phase (defined at the
  * masked positions of each window only). */
 int dllm_debug_logits(dllm_handle *h, const void **logits);

@@ -133,7 +133,9 @@ int check_commit_list(dllm_handle *h, const dllm_commit_list *o, CommitOut *c)
     return DLLM_OK;
 }
 
-int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens)
+// `win` (nullable): per-sequence windows; the vocabulary projection then only
+// covers the rows lo..hi of each sequence (the rows the selector reads).
+int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const SelectArgs *win)
 {
     const dllm_config &c = h->cfg;
     const int M = B * L, d = c.d_model, f = c.d_ffn;
@@ -157,7 +159,25 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens)
         pending = gemm_num_splits(M, d, f);
     }
     HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, M, d, c.rms_eps));
-    HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, h->lm_head, w.logits, M, c.vocab, d));
+    if (!win) {
+        HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, h->lm_head, w.logits, M, c.vocab, d));
+    } else {
+        // merge sequences whose windows make one contiguous run of rows (always true for B = 1)
+        int b = 0;
+        while (b < B) {
+            if (win->w[b].hi < win->w[b].lo) { ++b; continue; }
+            const long first = (long)b * L + win->w[b].lo;
+            long last = (long)b * L + win->w[b].hi;
+            int e = b + 1;
+            while (e < B && win->w[e].hi >= win->w[e].lo && (long)e * L + win->w[e].lo == last + 1) {
+                last = (long)e * L + win->w[e].hi;
+                ++e;
+            }
+            HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h + first * d, h->lm_head, w.logits + first * (long)c.vocab,
+                                   (int)(last - first + 1), c.vocab, d));
+            b = e;
+        }
+    }
     h->last_B = B;
     h->last_L = L;
     return DLLM_OK;
@@ -348,7 +368,7 @@ int dllm_forward(dllm_handle *h, int32_t B, int32_t L, const int32_t *tokens)
     int rc = check_batch(h, B, L);
     if (rc) return rc;
     if (!tokens) return fail(h, DLLM_EINVAL, "dllm_forward: tokens is null");
-    return forward_impl(h, B, L, tokens);
+    return forward_impl(h, B, L, tokens, nullptr);
 }
 
 int dllm_step(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *mask, int32_t *prev_pred,
@@ -361,7 +381,7 @@ int dllm_step(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *ma
     if ((rc = check_commit_list(h, out, &co))) return rc;
     SelectArgs args;
     if ((rc = build_select_args(h, B, L, sp, out->capacity, &args))) return rc;
-    if ((rc = forward_impl(h, B, L, tokens))) return rc;
+    if ((rc = forward_impl(h, B, L, tokens, &args))) return rc;
     HIP_TRY(h, launch_row_phase(h->stream, h->ws.logits, B, L, h->cfg.vocab, h->cfg.mask_id, mask, args, h->ws.pred,
                                 h->ws.conf));
     HIP_TRY(h, launch_seq_phase(h->stream, B, L, tokens, mask, prev_pred, h->ws.pred, h->ws.conf, args, co));

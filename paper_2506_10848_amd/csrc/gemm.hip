@@ -2,7 +2,9 @@
 //
 // Both operands are K-contiguous, which is what the 32x32x16 bf16 MFMA wants: a
 // lane feeds 8 consecutive K values of one row (A) or one column (W).  A
-// workgroup of 4 waves owns a BM x BN tile and walks K in steps of 64 through a
+// workgroup of 4 or 8 waves owns a BM x BN tile (8 waves, two per SIMD, keep the
+// LDS pipe busier: a single wave per SIMD cannot keep enough fragment reads in
+// flight) and walks K in steps of 64 through a
 // multi-stage LDS ring.
 //
 // Main kernel (gemm_dl_kernel, K % 64 == 0):
@@ -36,7 +38,6 @@ namespace dllm {
 
 namespace {
 
-constexpr int kThreads = 256;
 constexpr int kBK = 64;           // K elements per LDS stage
 constexpr int kChunksPerRow = 8;  // 16-byte chunks in a 64-element bf16 row
 
@@ -180,18 +181,20 @@ __device__ __forceinline__ int w_frag_row(int j, int wn, int l32)
 
 // ---- main kernel: K % 64 == 0, k_per_split % 64 == 0 --------------------------
 template <int BM, int BN, int WM, int WN, int NST, int EPI>
-__global__ __launch_bounds__(kThreads) void gemm_dl_kernel(const uint16_t *__restrict__ A,
+__global__ __launch_bounds__(WM * WN * 64) void gemm_dl_kernel(const uint16_t *__restrict__ A,
                                                            const uint16_t *__restrict__ W, void *__restrict__ Cout,
                                                            int M, int N, int K, int k_per_split, int num_m, int num_n)
 {
-    static_assert(WM * WN == 4, "4 waves per workgroup");
+    constexpr int NW = WM * WN;
+    static_assert(NW == 4 || NW == 8, "4 or 8 waves per workgroup");
     constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
     static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 MFMA tiles");
     static_assert(EPI != kEpiSwiglu || TN % 2 == 0, "SwiGLU pairs gate/up sub-tiles");
-    static_assert(BM % 32 == 0 && BN % 32 == 0 && NST >= 2 && NST <= 4, "stage shape");
-    constexpr int ROWS = BM + BN;      // rows of one stage: the A tile, then the W tile
-    constexpr int LOADS = ROWS / 32;   // 1 KB copies per wave per stage
-    constexpr int A_LOADS = BM / 32;
+    static_assert(NST >= 2 && NST <= 4, "stage count");
+    constexpr int ROWS = BM + BN;             // rows of one stage: the A tile, then the W tile
+    constexpr int LOADS = ROWS / (8 * NW);    // 1 KB copies per wave per stage
+    constexpr int A_LOADS = BM / (8 * NW);
+    static_assert(ROWS % (8 * NW) == 0 && BM % (8 * NW) == 0, "whole 8-row groups per wave");
     constexpr int STAGE = ROWS * kChunksPerRow;  // uint4 per stage
     extern __shared__ uint4 smem[];
 
@@ -208,14 +211,14 @@ __global__ __launch_bounds__(kThreads) void gemm_dl_kernel(const uint16_t *__res
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, lhalf = lane >> 5;
 
-    // wave w copies the 8-row groups w, w+4, ...; lane l lands on row l/8, slot l%8
+    // wave w copies the 8-row groups w, w+NW, ...; lane l lands on row l/8, slot l%8
     // of its group and therefore fetches the chunk that the swizzle puts there
     const int lrow = lane >> 3;
     const int kc = (lane & 7) ^ (((wave & 1) << 2) | (lrow >> 1));
     uint32_t goff[LOADS];  // byte offsets into A (first A_LOADS) or W; rows past the edge are clamped
 #pragma unroll
     for (int t = 0; t < LOADS; ++t) {
-        const int r = 8 * (wave + 4 * t) + lrow;
+        const int r = 8 * (wave + NW * t) + lrow;
         int grow;
         if (t < A_LOADS) {
             grow = min(m0 + r, M - 1);
@@ -234,7 +237,7 @@ __global__ __launch_bounds__(kThreads) void gemm_dl_kernel(const uint16_t *__res
         const char *pa_ = Ab + (size_t)(kt_) * (kBK * 2), *pw_ = Wb + (size_t)(kt_) * (kBK * 2); \
         const uint32_t dst_ = lds_addr_of(smem + (stage_) * STAGE + wave * 64);              \
         _Pragma("unroll") for (int t = 0; t < LOADS; ++t)                                    \
-            async_load16(t < A_LOADS ? pa_ : pw_, goff[t], dst_ + t * 4096);                 \
+            async_load16(t < A_LOADS ? pa_ : pw_, goff[t], dst_ + t * (NW * 1024));                 \
     } while (0)
 
     floatx16 acc[TM][TN];
@@ -296,16 +299,17 @@ __global__ __launch_bounds__(kThreads) void gemm_dl_kernel(const uint16_t *__res
 
 // ---- fallback kernel: any K % 8 == 0 -------------------------------------------
 template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__(kThreads) void gemm_reg_kernel(const uint16_t *__restrict__ A,
+__global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *__restrict__ A,
                                                             const uint16_t *__restrict__ W, void *__restrict__ Cout,
                                                             int M, int N, int K, int k_per_split, int num_m, int num_n)
 {
-    static_assert(WM * WN == 4, "4 waves per workgroup");
+    constexpr int kThreads = WM * WN * 64, RPL = kThreads / kChunksPerRow;  // rows covered by one load of all threads
     constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
     static_assert(EPI != kEpiSwiglu || (TN % 2 == 0), "SwiGLU pairs gate/up sub-tiles");
     constexpr int ROWS = BM + BN;
-    constexpr int LOADS = ROWS * kChunksPerRow / kThreads;
-    constexpr int A_LOADS = BM * kChunksPerRow / kThreads;
+    constexpr int LOADS = ROWS / RPL;
+    constexpr int A_LOADS = BM / RPL;
+    static_assert(ROWS % RPL == 0 && BM % RPL == 0, "whole loads");
     constexpr int STAGE = ROWS * kChunksPerRow;
     extern __shared__ uint4 smem[];
 
@@ -322,12 +326,12 @@ __global__ __launch_bounds__(kThreads) void gemm_reg_kernel(const uint16_t *__re
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, lhalf = lane >> 5;
 
-    const int ld_row = tid >> 3, ld_kc = tid & 7;  // + 32 rows per extra load
+    const int ld_row = tid >> 3, ld_kc = tid & 7;  // + RPL rows per extra load
     const uint16_t *src[LOADS];
     bool ok[LOADS];
 #pragma unroll
     for (int t = 0; t < LOADS; ++t) {
-        const int r = ld_row + t * 32;
+        const int r = ld_row + t * RPL;
         int grow;
         if (t < A_LOADS) {
             ok[t] = m0 + r < M;
@@ -364,7 +368,7 @@ __global__ __launch_bounds__(kThreads) void gemm_reg_kernel(const uint16_t *__re
             uint4 *dst = smem + ((kt - 1) & 1) * STAGE;
 #pragma unroll
             for (int t = 0; t < LOADS; ++t) {
-                const int r = ld_row + t * 32;
+                const int r = ld_row + t * RPL;
                 dst[r * kChunksPerRow + (ld_kc ^ ((r >> 1) & 7))] = reg[t];
             }
         }
@@ -402,13 +406,14 @@ __global__ __launch_bounds__(kThreads) void gemm_reg_kernel(const uint16_t *__re
 // measured on MI355X at M = 512 (copy and math of a step overlap only partly:
 // the LDS port is shared by the asynchronous copies and the fragment reads).
 struct TileCfg {
-    int bm, bn, nst;
+    int bm, bn, nst, waves;
     float step_clk, epi_clk;
 };
-constexpr int kNumCfg = 6;
+constexpr int kNumCfg = 7;
 const TileCfg kCfg[kNumCfg] = {
-    {256, 256, 2, 3580.f, 24000.f}, {256, 192, 2, 2870.f, 18000.f}, {256, 128, 3, 2120.f, 11800.f},
-    {256, 96, 3, 1950.f, 8900.f},   {128, 128, 3, 1300.f, 5800.f},  {128, 64, 4, 800.f, 3000.f},
+    {256, 256, 2, 8, 3180.f, 24000.f}, {256, 192, 2, 8, 2670.f, 18000.f}, {256, 128, 3, 8, 1730.f, 11800.f},
+    {256, 128, 3, 8, 1880.f, 11800.f}, {256, 96, 3, 4, 1950.f, 8900.f},   {128, 128, 3, 8, 1175.f, 5800.f},
+    {128, 64, 4, 4, 800.f, 3000.f},
 };
 constexpr int kNumCU = 256;
 constexpr int kLdsPerCU = 160 * 1024;
@@ -426,9 +431,10 @@ int env_int(const char *name, int dflt)
 
 bool cfg_allows(int c, GemmEpilogue epi, bool fast)
 {
-    if (epi == kEpiSwiglu && c == 3) return false;   // 256x96 as 4x1 waves: odd number of sub-tiles per wave
+    if (epi == kEpiSwiglu && c == 4) return false;   // 256x96 as 4x1 waves: odd number of sub-tiles per wave
     if (epi == kEpiPartial && c == 0) return false;  // 256x256 fp32 epilogue runs out of registers
     if (!fast && c < 2) return false;                // the register-staged kernel keeps to the smaller tiles
+    if (epi != kEpiPartial && c == 3) return false;  // 256x128 as 8x1 waves only pays off for the split-K shapes
     return true;
 }
 
@@ -441,7 +447,7 @@ Plan make_plan(GemmEpilogue epi, int M, int N, int K)
     const bool fast = (K % kBK == 0) && ((double)M * K * 2 < 4.0e9) && ((double)N * K * 2 < 4.0e9) &&
                       env_int("DLLM_GEMM_FALLBACK", 0) == 0;
     const int fc = env_int("DLLM_GEMM_CFG", -1), fs = env_int("DLLM_GEMM_SPLITS", -1);
-    Plan best{4, 1, fast};
+    Plan best{5, 1, fast};
     double best_cost = 1e300;
     const int max_splits = epi == kEpiPartial ? 8 : 1;
     for (int c = 0; c < kNumCfg; ++c) {
@@ -472,7 +478,7 @@ hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *
     const int n_out = EPI == kEpiSwiglu ? N / 2 : N;
     const int num_m = (M + BM - 1) / BM, num_n = (n_out + BN_OUT - 1) / BN_OUT;
     const int kps = ((K + splits - 1) / splits + kBK - 1) / kBK * kBK;
-    const dim3 grid(num_m * num_n, splits), block(kThreads);
+    const dim3 grid(num_m * num_n, splits), block(WM * WN * 64);
     if (fast) {
         const size_t lds = (size_t)NST * (BM + BN) * kChunksPerRow * sizeof(uint4);
         auto kern = gemm_dl_kernel<BM, BN, WM, WN, NST, EPI>;
@@ -505,13 +511,14 @@ template <int EPI>
 hipError_t dispatch(hipStream_t stream, Plan p, const void *A, const void *W, void *C, int M, int N, int K)
 {
     switch (p.cfg) {
-    case 0: return launch_cfg<256, 256, 2, 2, 2, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
-    case 1: return launch_cfg<256, 192, 4, 1, 2, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
-    case 2: return launch_cfg<256, 128, 2, 2, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
-    case 3:
+    case 0: return launch_cfg<256, 256, 4, 2, 2, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
+    case 1: return launch_cfg<256, 192, 8, 1, 2, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
+    case 2: return launch_cfg<256, 128, 4, 2, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
+    case 3: return launch_cfg<256, 128, 8, 1, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
+    case 4:
         if constexpr (EPI != kEpiSwiglu) return launch_cfg<256, 96, 4, 1, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
         return hipErrorInvalidValue;
-    case 4: return launch_cfg<128, 128, 2, 2, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
+    case 5: return launch_cfg<128, 128, 4, 2, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
     default: return launch_cfg<128, 64, 4, 1, 4, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
     }
 }

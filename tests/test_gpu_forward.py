@@ -58,7 +58,7 @@ GEMM_SHAPES = [  # M, N, K
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("fallback", [0, 1])
 def test_linear(M, N, K, tile, fallback, monkeypatch):
     """Every tile shape, through the asynchronous-copy kernel (K % 64 == 0) and
@@ -76,7 +76,7 @@ def test_linear(M, N, K, tile, fallback, monkeypatch):
 
 
 @pytest.mark.parametrize("M,f,K", [(96, 688, 256), (130, 200, 128), (512, 1408, 512)])
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 4, 5])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 5, 6])
 @pytest.mark.parametrize("fallback", [0, 1])
 def test_linear_swiglu(M, f, K, tile, fallback, monkeypatch):
     b = binding()
