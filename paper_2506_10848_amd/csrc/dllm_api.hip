@@ -145,8 +145,12 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const Sele
     int pending = 0;  // fp32 slabs waiting to be added to the residual stream
     for (int l = 0; l < c.n_layers; ++l) {
         HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->attn_norm[l], w.h, M, d, c.rms_eps));
-        HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, h->wqkv[l], w.qkv, M, 3 * d, d));
-        HIP_TRY(h, launch_rope(st, w.qkv, w.rope, B, L, c.n_heads, c.head_dim, c.rope_theta));
+        if (gemm_qkv_rope_supported(M, d, c.head_dim)) {
+            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, h->wqkv[l], w.qkv, M, d, c.head_dim, w.rope, L));
+        } else {
+            HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, h->wqkv[l], w.qkv, M, 3 * d, d));
+            HIP_TRY(h, launch_rope(st, w.qkv, w.rope, B, L, c.n_heads, c.head_dim, c.rope_theta));
+        }
         HIP_TRY(h, launch_attention(st, w.qkv, w.att, B, L, c.n_heads, c.head_dim));
         HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, M, d, d));
         pending = gemm_num_splits(M, d, d);

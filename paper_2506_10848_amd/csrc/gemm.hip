@@ -86,14 +86,53 @@ __device__ __forceinline__ void tile_of(int pid, int num_m, int num_n, int &pid_
     }
 }
 
+// Rotary embedding fused into the QKV projection's epilogue (kEpiRope): output
+// columns below rope_cols (the q and k thirds) are rotated in fp32 before the
+// bf16 rounding; pos = row % L, table[pos][j] = (cos, sin) of pos * theta^(-2j/dh).
+struct RopeArgs {
+    const float2 *table;
+    int L, dh, rope_cols;
+};
+constexpr int kEpiRope64 = 3, kEpiRope128 = 4;  // head_dim is a compile-time constant of the epilogue
+
 // Accumulators hold the transposed 32x32 tiles: element e of lane l is output
 // row l % 32, column 8*(e/4) + 4*(l/32) + e%4.
 template <int TM, int TN, int WTM, int WTN, int EPI>
 __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, int M, int N, int n_out, int m0, int n0,
-                                           int wm, int wn, int l32, int lhalf, int split)
+                                           int wm, int wn, int l32, int lhalf, int split, const RopeArgs &rope)
 {
     constexpr int HALF_TN = TN / 2 > 0 ? TN / 2 : 1;
-    if (EPI == kEpiBf16) {
+    if (EPI == kEpiRope64 || EPI == kEpiRope128) {
+        // the wave holds whole heads: columns c and c + DH/2 of a head sit in sub-tiles j and
+        // j + PJ, same lane, same element
+        constexpr int DH = EPI == kEpiRope128 ? 128 : 64, PJ = DH / 64;
+        if (n0 + wn * WTN < rope.rope_cols) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row = m0 + wm * WTM + i * 32 + l32;
+                const float2 *trow = rope.table + (size_t)(row % rope.L) * (DH / 2) + 4 * lhalf;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    if ((j / PJ) & 1) continue;  // second half of a head: handled with its partner
+                    constexpr int TNm = TN;      // (keeps the partner index inside the array for every instantiation)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        // four consecutive (cos, sin) pairs: 32 bytes
+                        const float4 *tp = reinterpret_cast<const float4 *>(trow + ((j * 32) % DH) + 8 * q);
+                        const float4 t01 = tp[0], t23 = tp[1];
+                        const float cs[4] = {t01.x, t01.z, t23.x, t23.z}, sn[4] = {t01.y, t01.w, t23.y, t23.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float a = acc[i][j][4 * q + e], b = acc[i][(j + PJ) % TNm][4 * q + e];
+                            acc[i][j][4 * q + e] = a * cs[e] - b * sn[e];
+                            acc[i][(j + PJ) % TNm][4 * q + e] = a * sn[e] + b * cs[e];
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if (EPI == kEpiBf16 || EPI == kEpiRope64 || EPI == kEpiRope128) {
         uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -183,7 +222,8 @@ __device__ __forceinline__ int w_frag_row(int j, int wn, int l32)
 template <int BM, int BN, int WM, int WN, int NST, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_dl_kernel(const uint16_t *__restrict__ A,
                                                            const uint16_t *__restrict__ W, void *__restrict__ Cout,
-                                                           int M, int N, int K, int k_per_split, int num_m, int num_n)
+                                                           int M, int N, int K, int k_per_split, int num_m, int num_n,
+                                                           RopeArgs rope)
 {
     constexpr int NW = WM * WN;
     static_assert(NW == 4 || NW == 8, "4 or 8 waves per workgroup");
@@ -294,14 +334,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dl_kernel(const uint16_t *_
         }
     }
 #undef DLLM_ISSUE_STAGE
-    store_tile<TM, TN, WTM, WTN, EPI>(acc, Cout, M, N, n_out, m0, n0, wm, wn, l32, lhalf, blockIdx.y);
+    store_tile<TM, TN, WTM, WTN, EPI>(acc, Cout, M, N, n_out, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
 }
 
 // ---- fallback kernel: any K % 8 == 0 -------------------------------------------
 template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *__restrict__ A,
                                                             const uint16_t *__restrict__ W, void *__restrict__ Cout,
-                                                            int M, int N, int K, int k_per_split, int num_m, int num_n)
+                                                            int M, int N, int K, int k_per_split, int num_m, int num_n,
+                                                            RopeArgs rope)
 {
     constexpr int kThreads = WM * WN * 64, RPL = kThreads / kChunksPerRow;  // rows covered by one load of all threads
     constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
@@ -397,7 +438,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
     }
-    store_tile<TM, TN, WTM, WTN, EPI>(acc, Cout, M, N, n_out, m0, n0, wm, wn, l32, lhalf, blockIdx.y);
+    store_tile<TM, TN, WTM, WTN, EPI>(acc, Cout, M, N, n_out, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
 }
 
 // ---- host side ----------------------------------------------------------------
@@ -472,7 +513,7 @@ Plan make_plan(GemmEpilogue epi, int M, int N, int K)
 
 template <int BM, int BN, int WM, int WN, int NST, int EPI>
 hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *W, void *C, int M, int N, int K,
-                      int splits)
+                      int splits, RopeArgs rope = RopeArgs{nullptr, 1, 64, 0})
 {
     constexpr int BN_OUT = EPI == kEpiSwiglu ? BN / 2 : BN;
     const int n_out = EPI == kEpiSwiglu ? N / 2 : N;
@@ -490,7 +531,7 @@ hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *
             attr_done = true;
         }
         hipLaunchKernelGGL(kern, grid, block, lds, stream, (const uint16_t *)A, (const uint16_t *)W, C, M, N, K, kps,
-                           num_m, num_n);
+                           num_m, num_n, rope);
     } else {
         const size_t lds = (size_t)2 * (BM + BN) * kChunksPerRow * sizeof(uint4);
         auto kern = gemm_reg_kernel<BM, BN, WM, WN, EPI>;
@@ -502,7 +543,7 @@ hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *
             attr_done = true;
         }
         hipLaunchKernelGGL(kern, grid, block, lds, stream, (const uint16_t *)A, (const uint16_t *)W, C, M, N, K, kps,
-                           num_m, num_n);
+                           num_m, num_n, rope);
     }
     return hipGetLastError();
 }
@@ -526,6 +567,22 @@ hipError_t dispatch(hipStream_t stream, Plan p, const void *A, const void *W, vo
 }  // namespace
 
 int gemm_num_splits(int M, int N, int K) { return make_plan(kEpiPartial, M, N, K).splits; }
+
+bool gemm_qkv_rope_supported(int M, int d, int dh)
+{
+    // whole heads per 128-column tile, q/k boundary on a tile edge, asynchronous-copy kernel
+    return (dh == 64 || dh == 128) && d % 128 == 0 && d % kBK == 0 && (double)M * d * 2 < 4.0e9 &&
+           (double)3 * d * d * 2 < 4.0e9 && env_int("DLLM_GEMM_FALLBACK", 0) == 0 && env_int("DLLM_NO_FUSED_ROPE", 0) == 0;
+}
+
+hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
+                                const float2 *table, int L)
+{
+    // 256x128 tile as 8x1 waves: a wave owns 32 rows x 128 columns = whole heads
+    const RopeArgs rope{table, L, dh, 2 * d};
+    if (dh == 128) return launch_cfg<256, 128, 8, 1, 3, kEpiRope128>(stream, true, A, W, C, M, 3 * d, d, 1, rope);
+    return launch_cfg<256, 128, 8, 1, 3, kEpiRope64>(stream, true, A, W, C, M, 3 * d, d, 1, rope);
+}
 
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
                        int K)

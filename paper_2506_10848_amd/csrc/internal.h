@@ -48,6 +48,11 @@ enum GemmEpilogue {
 };
 // How many K splits launch_gemm will use for a kEpiPartial problem (>= 1).
 int gemm_num_splits(int M, int N, int K);
+// QKV projection with the rotary embedding of the q and k thirds fused into the
+// epilogue: C bf16 [M][3d] = A[M][d] * W[3d][d]^T, rows are positions row % L.
+bool gemm_qkv_rope_supported(int M, int d, int dh);
+hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
+                                const float2 *table, int L);
 // C = A[M][K] * W[N][K]^T.  For kEpiSwiglu N counts gate + up rows.
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
                        int K);

@@ -207,6 +207,18 @@ def test_forward_tiny_config():
     logits_close(got, ref)
 
 
+def test_forward_tiny_config_unfused_rope_and_fallback_gemm(monkeypatch):
+    """The same forward through the separate RoPE kernel, and through the
+    register-staged GEMM kernel everywhere."""
+    cfg = synth.CONFIGS["tiny"]
+    monkeypatch.setenv("DLLM_NO_FUSED_ROPE", "1")
+    got, ref = run_forward(cfg, cfg["batch"])
+    logits_close(got, ref)
+    monkeypatch.setenv("DLLM_GEMM_FALLBACK", "1")
+    got, ref = run_forward(cfg, 2)
+    logits_close(got, ref)
+
+
 def test_forward_tiny_config_wide_init_batch3():
     cfg = synth.CONFIGS["tiny"]
     got, ref = run_forward(cfg, 3, std=0.06)        # larger activations, stronger attention
