@@ -110,7 +110,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="llada8b", choices=["llada8b", "medium", "tiny"])
+    ap.add_argument("--workload", default="llada8b", choices=["llada8b", "llada8b_long", "medium", "tiny"])
     ap.add_argument("--no-extras", action="store_true", help="skip decode / selector / cpu baseline legs")
     ap.add_argument("--selector-only", action="store_true",
                     help="run only the selector workload (16 x 2048 x 126464 logits) and print its line")
