@@ -218,6 +218,13 @@ int dllm_op_add_rmsnorm(void *hip_stream, float *x, const float *partials, int32
                         const void *gain, void *h, int32_t M, int32_t d, float eps);
 /* In-place RoPE on the q and k thirds of qkv bf16 [B*L][3*H*dh]. */
 int dllm_op_rope(void *hip_stream, void *qkv, int32_t B, int32_t L, int32_t H, int32_t dh, float theta);
+/* Fused QKV projection + RoPE (Section 2.1's bidirectional transformer block; rotary embedding
+ * as in LLaDA): qkv bf16 [B*L][3*H*dh] = A[B*L][H*dh] * W[3*H*dh][H*dh]^T with the q and k thirds
+ * rotated in fp32 before the single bf16 rounding; row r has position r % L.  `table` is scratch
+ * the caller provides, float [L][dh/2][2] dev, filled with (cos, sin) by this call.
+ * DLLM_EINVAL if the fused kernel does not cover the shape (dh not 64/128, (H*dh) % 64 != 0). */
+int dllm_op_linear_qkv_rope(void *hip_stream, const void *A, const void *W, void *qkv, float *table,
+                            int32_t B, int32_t L, int32_t H, int32_t dh, float theta);
 /* Non-causal attention: qkv bf16 [B*L][3*H*dh] -> out bf16 [B*L][H*dh]. */
 int dllm_op_attention(void *hip_stream, const void *qkv, void *out, int32_t B, int32_t L, int32_t H, int32_t dh);
 

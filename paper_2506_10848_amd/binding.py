@@ -62,7 +62,7 @@ class StepStat(C.Structure):
 
 EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_decode", "dllm_debug_logits",
            "dllm_debug_rows", "dllm_profile_begin", "dllm_profile_end", "dllm_forward", "dllm_select", "dllm_op_linear", "dllm_op_linear_swiglu",
-           "dllm_op_add_rmsnorm", "dllm_op_rope", "dllm_op_attention"]
+           "dllm_op_add_rmsnorm", "dllm_op_rope", "dllm_op_linear_qkv_rope", "dllm_op_attention"]
 
 _lib = None
 
@@ -273,6 +273,15 @@ def op_add_rmsnorm(x, partials, gain, eps: float):
     _check(lib().dllm_op_add_rmsnorm(_stream(), _ptr(x), _ptr(partials), n, _ptr(gain), _ptr(h), M, d,
                                      C.c_float(eps)))
     return h
+
+
+def op_linear_qkv_rope(A, W, B: int, L: int, H: int, dh: int, theta: float):
+    _dev(A, torch.bfloat16, "A"); _dev(W, torch.bfloat16, "W")
+    qkv = torch.empty((B * L, 3 * H * dh), dtype=torch.bfloat16, device=A.device)
+    table = torch.empty((L, dh // 2, 2), dtype=torch.float32, device=A.device)
+    _check(lib().dllm_op_linear_qkv_rope(_stream(), _ptr(A), _ptr(W), _ptr(qkv), _ptr(table), B, L, H, dh,
+                                         C.c_float(theta)))
+    return qkv
 
 
 def op_rope(qkv, B: int, L: int, H: int, dh: int, theta: float):

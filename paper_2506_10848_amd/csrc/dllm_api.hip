@@ -571,6 +571,23 @@ int dllm_op_rope(void *hip_stream, void *qkv, int32_t B, int32_t L, int32_t H, i
     return DLLM_OK;
 }
 
+int dllm_op_linear_qkv_rope(void *hip_stream, const void *A, const void *W, void *qkv, float *table, int32_t B,
+                            int32_t L, int32_t H, int32_t dh, float theta)
+{
+    if (!A || !W || !qkv || !table) return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_qkv_rope: null argument");
+    if (!aligned16(A) || !aligned16(W) || !aligned16(qkv) || !aligned16(table))
+        return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_qkv_rope: pointers must be 16-byte aligned");
+    if (B < 1 || L < 1 || H < 1 || !(theta > 0.0f) || (long)B * L > (1L << 24) || (long)H * dh > (1L << 20))
+        return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_qkv_rope: bad shape");
+    const int M = B * L, d = H * dh;
+    if (!gemm_qkv_rope_supported(M, d, dh))
+        return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_qkv_rope: shape not covered by the fused kernel");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    HIP_TRY(nullptr, launch_rope_table(st, reinterpret_cast<float2 *>(table), L, dh, theta));
+    HIP_TRY(nullptr, launch_gemm_qkv_rope(st, A, W, qkv, M, d, dh, reinterpret_cast<const float2 *>(table), L));
+    return DLLM_OK;
+}
+
 int dllm_op_attention(void *hip_stream, const void *qkv, void *out, int32_t B, int32_t L, int32_t H, int32_t dh)
 {
     if (!qkv || !out || !aligned16(qkv) || !aligned16(out)) return fail(nullptr, DLLM_EINVAL, "dllm_op_attention: null or misaligned pointer");

@@ -2,34 +2,52 @@
 //
 // Both operands are K-contiguous, which is what the 32x32x16 bf16 MFMA wants: a
 // lane feeds 8 consecutive K values of one row (A) or one column (W).  A
-// workgroup of 4 or 8 waves owns a BM x BN tile (8 waves, two per SIMD, keep the
-// LDS pipe busier: a single wave per SIMD cannot keep enough fragment reads in
-// flight) and walks K in steps of 64 through a
-// multi-stage LDS ring.
+// workgroup of four waves (2x2 or 4x1, one wave per SIMD) owns a BM x BN tile
+// and walks K in stages of BK = 32 or 64 through an LDS ring of NST stages.
+// Large wave tiles (up to 128x128) keep the LDS fragment traffic per flop low:
+// under MFMA load the chip is power limited (measured shader clocks of 1.4 to
+// 1.8 GHz), so bytes moved per flop decide the sustained rate as much as issue
+// slots do.
 //
-// Main kernel (gemm_dl_kernel, K % 64 == 0):
+// Main kernel (gemm_il_kernel, K % 64 == 0):
 //   * global -> LDS copies are asynchronous (global_load_lds_dwordx4, 1 KB per
-//     wave instruction, no VGPR staging) and run NST-1 K-steps ahead of the math;
-//     the only per-step synchronisation is one s_waitcnt vmcnt + one s_barrier.
-//   * LDS rows are 128 bytes; 16-byte chunks are XOR-swizzled with (row >> 1) & 7.
-//     The LDS has 64 banks and serves 16 lanes x 16 bytes per cycle, i.e. two rows
-//     per cycle, so this keeps the fragment reads of 16 consecutive rows on 64
-//     distinct banks.  The swizzle is applied by choosing which global chunk each
-//     lane copies, because the LDS side of the copy is fixed (lane * 16 bytes).
-//   * fragments for K-substep kk+1 are requested before the MFMAs of substep kk
-//     (scheduling barriers keep the compiler from sinking the reads again).
+//     wave instruction, no VGPR staging) and run NST-1 stages ahead of the math.
+//   * One wave per SIMD means nothing else fills an issue bubble, so the stream
+//     is software-pipelined by hand: the fragment reads for the next K-substep
+//     and the copies of a later stage are spread one by one between the MFMAs
+//     of the current substep (an LDS read or copy issued right after an MFMA
+//     costs nothing, a clump of them stalls the matrix pipe), and the only
+//     barrier of a stage sits in front of the last substep's MFMAs, which hide
+//     it together with the first fragment reads of the next stage.
+//   * The loop is split into a steady state (every step issues copies) and a
+//     tail (none left), so there is no branch between MFMAs; wait counts are
+//     compile-time constants in the steady state.
+//   * LDS rows are BK*2 bytes; 16-byte chunks are XOR-swizzled ((row >> 1) & 7
+//     for 128-byte rows, (row >> 2) & 3 for 64-byte rows): the LDS has 64 banks
+//     and serves 16 lanes x 16 bytes per cycle, and this keeps each such group
+//     of fragment reads on 64 distinct banks.  The swizzle is applied by
+//     choosing which global chunk each lane copies, because the LDS side of the
+//     copy is fixed (lane * 16 bytes).
 //   * MFMAs are issued as (W fragment) x (A fragment): the accumulators then hold
 //     the transposed tile, four consecutive output columns per lane, and the
 //     epilogue stores 8 (bf16) or 16 (fp32) bytes per lane.
+//   * Every kernel argument is forced into registers before the loop: a scalar
+//     load still pending at the loop header shares its counter with the LDS
+//     reads and would make the compiler wait for all of them at every use.
 // Fallback kernel (gemm_reg_kernel): any K % 8 == 0, register-staged loads with
 // zero fill, two LDS stages.
 //
-// Epilogues: bf16 store; SwiGLU (a tile carries the gate and the up columns of
-// the same features, so silu(gate) * up is formed in registers); fp32 slabs for
-// split-K, which the next residual-add + RMSNorm kernel sums.
+// Epilogues: bf16 store; fp32 slabs for split-K, which the next residual-add +
+// RMSNorm kernel sums; and two "paired" epilogues, SwiGLU and rotary embedding,
+// that combine two output columns.  For those the W rows of a tile are permuted
+// while they are copied: every 32-row MFMA tile holds 16 first partners (gate
+// rows; first half of a head) followed by their 16 second partners (up rows;
+// second half of the head), so both values of a pair end up in the same lane,
+// 8 accumulator elements apart, whatever the wave layout.
 //
 // Workgroup ids are mapped so that the tiles sharing a weight column block run on
 // the same XCD (ids congruent mod 8 share an L2).
+#include <stdio.h>
 #include <stdlib.h>
 
 #include "internal.h"
@@ -37,9 +55,6 @@
 namespace dllm {
 
 namespace {
-
-constexpr int kBK = 64;           // K elements per LDS stage
-constexpr int kChunksPerRow = 8;  // 16-byte chunks in a 64-element bf16 row
 
 #define DLLM_LDS_VOID(p) ((__attribute__((address_space(3))) void *)(p))
 
@@ -70,6 +85,17 @@ __device__ __forceinline__ void wait_vmcnt()
 {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
+// at most n * LOADS copies may still be in flight, n in [0, MAXN]
+template <int MAXN, int LOADS>
+__device__ __forceinline__ void wait_stages_after(int n)
+{
+    if constexpr (MAXN <= 0) {
+        wait_vmcnt<0>();
+    } else {
+        if (n >= MAXN) wait_vmcnt<(MAXN * LOADS > 63 ? 63 : MAXN * LOADS)>();
+        else wait_stages_after<MAXN - 1, LOADS>(n);
+    }
+}
 
 // tile of this workgroup; tiles that share W rows get ids congruent mod 8
 __device__ __forceinline__ void tile_of(int pid, int num_m, int num_n, int &pid_m, int &pid_n)
@@ -86,88 +112,57 @@ __device__ __forceinline__ void tile_of(int pid, int num_m, int num_n, int &pid_
     }
 }
 
-// Rotary embedding fused into the QKV projection's epilogue (kEpiRope): output
-// columns below rope_cols (the q and k thirds) are rotated in fp32 before the
-// bf16 rounding; pos = row % L, table[pos][j] = (cos, sin) of pos * theta^(-2j/dh).
+// Rotary embedding fused into the QKV projection's epilogue: output columns
+// below rope_cols (the q and k thirds) are rotated in fp32 before the bf16
+// rounding; pos = row % L, table[pos][j] = (cos, sin) of pos * theta^(-2j/dh).
 struct RopeArgs {
     const float2 *table;
-    int L, dh, rope_cols;
+    int L, rope_cols;
 };
 constexpr int kEpiRope64 = 3, kEpiRope128 = 4;  // head_dim is a compile-time constant of the epilogue
 
-// Accumulators hold the transposed 32x32 tiles: element e of lane l is output
-// row l % 32, column 8*(e/4) + 4*(l/32) + e%4.
-template <int TM, int TN, int WTM, int WTN, int EPI>
-__device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, int M, int N, int n_out, int m0, int n0,
-                                           int wm, int wn, int l32, int lhalf, int split, const RopeArgs &rope)
+__host__ __device__ constexpr bool epi_paired(int epi) { return epi == kEpiSwiglu || epi == kEpiRope64 || epi == kEpiRope128; }
+__host__ __device__ constexpr int epi_head_dim(int epi) { return epi == kEpiRope128 ? 128 : 64; }
+
+// Global W row held by row j of a workgroup's W tile.  Plain epilogues: n0 + j.
+// Paired epilogues: the tile covers pairs [pair0, pair0 + BN/2); MFMA tile s =
+// j / 32 holds pairs pair0 + 16 s .. + 15, first partners in its rows 0..15,
+// second partners in rows 16..31.  n_pairs = number of pairs of the whole
+// matrix (SwiGLU: features, the up row of feature p is n_pairs + p; rotary:
+// columns c and c + dh/2 of a head).  Rows past the edge are clamped.
+template <int EPI>
+__device__ __forceinline__ int w_global_row(int j, int n0, int N)
 {
-    constexpr int HALF_TN = TN / 2 > 0 ? TN / 2 : 1;
-    if (EPI == kEpiRope64 || EPI == kEpiRope128) {
-        // the wave holds whole heads: columns c and c + DH/2 of a head sit in sub-tiles j and
-        // j + PJ, same lane, same element
-        constexpr int DH = EPI == kEpiRope128 ? 128 : 64, PJ = DH / 64;
-        if (n0 + wn * WTN < rope.rope_cols) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int row = m0 + wm * WTM + i * 32 + l32;
-                const float2 *trow = rope.table + (size_t)(row % rope.L) * (DH / 2) + 4 * lhalf;
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    if ((j / PJ) & 1) continue;  // second half of a head: handled with its partner
-                    constexpr int TNm = TN;      // (keeps the partner index inside the array for every instantiation)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        // four consecutive (cos, sin) pairs: 32 bytes
-                        const float4 *tp = reinterpret_cast<const float4 *>(trow + ((j * 32) % DH) + 8 * q);
-                        const float4 t01 = tp[0], t23 = tp[1];
-                        const float cs[4] = {t01.x, t01.z, t23.x, t23.z}, sn[4] = {t01.y, t01.w, t23.y, t23.w};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float a = acc[i][j][4 * q + e], b = acc[i][(j + PJ) % TNm][4 * q + e];
-                            acc[i][j][4 * q + e] = a * cs[e] - b * sn[e];
-                            acc[i][(j + PJ) % TNm][4 * q + e] = a * sn[e] + b * cs[e];
-                        }
-                    }
-                }
-            }
-        }
-    }
-    if (EPI == kEpiBf16 || EPI == kEpiRope64 || EPI == kEpiRope128) {
+    if (!epi_paired(EPI)) return min(n0 + j, N - 1);
+    const int n_pairs = N / 2;
+    const int p = min(n0 + (j >> 5) * 16 + (j & 15), n_pairs - 1), second = (j >> 4) & 1;
+    if (EPI == kEpiSwiglu) return second * n_pairs + p;
+    constexpr int HD = epi_head_dim(EPI) / 2;
+    return (p / HD) * (2 * HD) + second * HD + p % HD;
+}
+
+// Accumulators hold the transposed 32x32 tiles: element e of lane l is output
+// row l % 32, tile column 8*(e/4) + 4*(l/32) + e%4.  n0 is the first output
+// column (plain) or the first pair (paired) of the workgroup's tile.
+template <int TM, int TN, int WTM, int EPI>
+__device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, int M, int N, int m0, int n0, int wm,
+                                           int wn, int l32, int lhalf, int split, const RopeArgs &rope)
+{
+    if (EPI == kEpiSwiglu) {
         uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
+        const int n_out = N / 2;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row = m0 + wm * WTM + i * 32 + l32;
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int col = n0 + wn * WTN + j * 32 + 8 * q + 4 * lhalf;
-                    if (row >= M || col >= N) continue;
-                    uint16_t *p = C + (size_t)row * N + col;
-                    if (col + 3 < N && (N & 3) == 0) {
-                        uint2 w;
-                        w.x = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
-                        w.y = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-                        *reinterpret_cast<uint2 *>(p) = w;
-                    } else {
-                        for (int e = 0; e < 4 && col + e < N; ++e) p[e] = float_to_bf16_bits(acc[i][j][4 * q + e]);
-                    }
-                }
-        }
-    } else if (EPI == kEpiSwiglu) {
-        uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int row = m0 + wm * WTM + i * 32 + l32;
-#pragma unroll
-            for (int j = 0; j < HALF_TN; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int col = n0 + wn * (WTN / 2) + j * 32 + 8 * q + 4 * lhalf;
+                for (int q = 0; q < 2; ++q) {
+                    const int col = n0 + (wn * TN + j) * 16 + 8 * q + 4 * lhalf;
                     float y[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float g = acc[i][j][4 * q + e], u = acc[i][j + HALF_TN][4 * q + e];
+                        const float g = acc[i][j][4 * q + e], u = acc[i][j][8 + 4 * q + e];
                         y[e] = g / (1.0f + __expf(-g)) * u;
                     }
                     if (row >= M || col >= n_out) continue;
@@ -182,6 +177,70 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
                     }
                 }
         }
+    } else if (EPI == kEpiRope64 || EPI == kEpiRope128) {
+        // N % head_dim == 0 and head_dim % 32 == 0 (checked by the host): the 4 pairs of a lane
+        // share a head, and whole 16-byte groups are inside or outside the matrix
+        constexpr int HD = epi_head_dim(EPI) / 2;
+        uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = m0 + wm * WTM + i * 32 + l32;
+            const float2 *trow = rope.table + (size_t)(row % rope.L) * HD;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int p = n0 + (wn * TN + j) * 16 + 8 * q + 4 * lhalf;  // first of the lane's 4 pairs
+                    const int pp = p % HD, col = (p / HD) * (2 * HD) + pp;
+                    if (row >= M || p >= N / 2) continue;
+                    float a[4], b[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        a[e] = acc[i][j][4 * q + e];
+                        b[e] = acc[i][j][8 + 4 * q + e];
+                    }
+                    if (col < rope.rope_cols) {
+                        const float4 *tp = reinterpret_cast<const float4 *>(trow + pp);  // 4 (cos, sin) pairs
+                        const float4 t01 = tp[0], t23 = tp[1];
+                        const float cs[4] = {t01.x, t01.z, t23.x, t23.z}, sn[4] = {t01.y, t01.w, t23.y, t23.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float x = a[e], y = b[e];
+                            a[e] = x * cs[e] - y * sn[e];
+                            b[e] = x * sn[e] + y * cs[e];
+                        }
+                    }
+                    uint2 w;
+                    w.x = pack_bf16x2(a[0], a[1]);
+                    w.y = pack_bf16x2(a[2], a[3]);
+                    *reinterpret_cast<uint2 *>(C + (size_t)row * N + col) = w;
+                    w.x = pack_bf16x2(b[0], b[1]);
+                    w.y = pack_bf16x2(b[2], b[3]);
+                    *reinterpret_cast<uint2 *>(C + (size_t)row * N + col + HD) = w;
+                }
+        }
+    } else if (EPI == kEpiBf16) {
+        uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = m0 + wm * WTM + i * 32 + l32;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = n0 + (wn * TN + j) * 32 + 8 * q + 4 * lhalf;
+                    if (row >= M || col >= N) continue;
+                    uint16_t *p = C + (size_t)row * N + col;
+                    if (col + 3 < N && (N & 3) == 0) {
+                        uint2 w;
+                        w.x = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+                        w.y = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                        *reinterpret_cast<uint2 *>(p) = w;
+                    } else {
+                        for (int e = 0; e < 4 && col + e < N; ++e) p[e] = float_to_bf16_bits(acc[i][j][4 * q + e]);
+                    }
+                }
+        }
     } else {
         float *C = reinterpret_cast<float *>(Cout) + (size_t)split * M * N;
 #pragma unroll
@@ -191,7 +250,7 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int col = n0 + wn * WTN + j * 32 + 8 * q + 4 * lhalf;
+                    const int col = n0 + (wn * TN + j) * 32 + 8 * q + 4 * lhalf;
                     if (row >= M || col >= N) continue;
                     float *p = C + (size_t)row * N + col;
                     if (col + 3 < N && (N & 3) == 0) {
@@ -205,79 +264,59 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
     }
 }
 
-// LDS row (in 16-byte chunks) of the W fragment j of wave column wn.  For the
-// SwiGLU epilogue the stage holds [gate rows | up rows] and a wave pairs the
-// same features from both halves.
-template <int BM, int BN, int WTN, int TN, int EPI>
-__device__ __forceinline__ int w_frag_row(int j, int wn, int l32)
-{
-    if (EPI == kEpiSwiglu) {
-        constexpr int HALF_TN = TN / 2 > 0 ? TN / 2 : 1;
-        return BM + (j / HALF_TN) * (BN / 2) + wn * (WTN / 2) + (j % HALF_TN) * 32 + l32;
-    }
-    return BM + wn * WTN + j * 32 + l32;
-}
-
-// ---- main kernel: K % 64 == 0, k_per_split % 64 == 0 --------------------------
-template <int BM, int BN, int WM, int WN, int NST, int EPI>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_dl_kernel(const uint16_t *__restrict__ A,
+// ---- main kernel: K % BK == 0, k_per_split % BK == 0 ---------------------------
+template <int BM, int BN, int WM, int WN, int BK, int NST, int EPI>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *__restrict__ A,
                                                            const uint16_t *__restrict__ W, void *__restrict__ Cout,
                                                            int M, int N, int K, int k_per_split, int num_m, int num_n,
                                                            RopeArgs rope)
 {
     constexpr int NW = WM * WN;
-    static_assert(NW == 4 || NW == 8, "4 or 8 waves per workgroup");
     constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
     static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 MFMA tiles");
-    static_assert(EPI != kEpiSwiglu || TN % 2 == 0, "SwiGLU pairs gate/up sub-tiles");
-    static_assert(NST >= 2 && NST <= 4, "stage count");
-    constexpr int ROWS = BM + BN;             // rows of one stage: the A tile, then the W tile
-    constexpr int LOADS = ROWS / (8 * NW);    // 1 KB copies per wave per stage
-    constexpr int A_LOADS = BM / (8 * NW);
-    static_assert(ROWS % (8 * NW) == 0 && BM % (8 * NW) == 0, "whole 8-row groups per wave");
-    constexpr int STAGE = ROWS * kChunksPerRow;  // uint4 per stage
+    static_assert(BK == 32 || BK == 64, "stage depth");
+    // 16-byte chunks per LDS row, K-substeps per stage, rows moved by one copy instruction of a wave
+    constexpr int CPR = BK / 8, KS = BK / 16, RPI = 64 / CPR;
+    constexpr int ROWS = BM + BN;  // rows of one stage: the A tile, then the W tile
+    constexpr int NI = ROWS / RPI, LOADS = NI / NW, A_NI = BM / RPI;
+    static_assert(ROWS % RPI == 0 && NI % NW == 0 && BM % RPI == 0, "whole copy instructions per wave");
+    constexpr int P = NST - 1;  // stages in flight ahead of the one being multiplied
+    static_assert(NST >= 3, "the stage after the current one is completely issued one step ahead");
+    static_assert(P * LOADS <= 63, "outstanding copies fit the wait counter");
+    constexpr int STAGE = ROWS * CPR;  // uint4 per stage
+    constexpr int NMF = TM * TN, NRD = TM + TN;
     extern __shared__ uint4 smem[];
 
     int pid_m, pid_n;
     tile_of(blockIdx.x, num_m, num_n, pid_m, pid_n);
-    constexpr int BN_OUT = (EPI == kEpiSwiglu) ? BN / 2 : BN;
+    constexpr int BN_OUT = epi_paired(EPI) ? BN / 2 : BN;  // output columns (plain) or pairs (paired) per tile
     const int m0 = pid_m * BM, n0 = pid_n * BN_OUT;
-    const int n_out = (EPI == kEpiSwiglu) ? N / 2 : N;
     const int kbeg = blockIdx.y * k_per_split;
     const int kend = min(K, kbeg + k_per_split);
-    const int nk = (kend - kbeg) / kBK;
+    const int nk = (kend - kbeg) / BK;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, lhalf = lane >> 5;
 
-    // wave w copies the 8-row groups w, w+NW, ...; lane l lands on row l/8, slot l%8
-    // of its group and therefore fetches the chunk that the swizzle puts there
-    const int lrow = lane >> 3;
-    const int kc = (lane & 7) ^ (((wave & 1) << 2) | (lrow >> 1));
-    uint32_t goff[LOADS];  // byte offsets into A (first A_LOADS) or W; rows past the edge are clamped
+    // copy instruction q = wave + NW * t moves LDS rows [q * RPI, (q + 1) * RPI); lane l lands on row
+    // l / CPR, slot l % CPR of that group and therefore fetches the chunk that the swizzle puts there
+    const int lrow = lane / CPR, lslot = lane % CPR;
+    uint32_t goff[LOADS];  // byte offsets into A or W; rows past the edge are clamped
 #pragma unroll
     for (int t = 0; t < LOADS; ++t) {
-        const int r = 8 * (wave + NW * t) + lrow;
-        int grow;
-        if (t < A_LOADS) {
-            grow = min(m0 + r, M - 1);
-        } else if (EPI == kEpiSwiglu) {
-            const int j = r - BM, half = j / (BN / 2), jj = j % (BN / 2);
-            grow = half * n_out + min(n0 + jj, n_out - 1);
-        } else {
-            grow = min(n0 + r - BM, N - 1);
-        }
-        goff[t] = (uint32_t)grow * (uint32_t)K * 2u + kc * 16;
+        const int q = wave + NW * t, r = q * RPI + lrow;
+        const int swz = BK == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3);
+        const int grow = q < A_NI ? min(m0 + r, M - 1) : w_global_row<EPI>(r - BM, n0, N);
+        goff[t] = (uint32_t)grow * (uint32_t)K * 2u + (lslot ^ swz) * 16;
     }
     const char *Ab = reinterpret_cast<const char *>(A) + (size_t)kbeg * 2;
     const char *Wb = reinterpret_cast<const char *>(W) + (size_t)kbeg * 2;
-#define DLLM_ISSUE_STAGE(kt_, stage_)                                                        \
-    do {                                                                                     \
-        const char *pa_ = Ab + (size_t)(kt_) * (kBK * 2), *pw_ = Wb + (size_t)(kt_) * (kBK * 2); \
-        const uint32_t dst_ = lds_addr_of(smem + (stage_) * STAGE + wave * 64);              \
-        _Pragma("unroll") for (int t = 0; t < LOADS; ++t)                                    \
-            async_load16(t < A_LOADS ? pa_ : pw_, goff[t], dst_ + t * (NW * 1024));                 \
+    const uint32_t lds0 = lds_addr_of(smem) + wave * 1024;
+#define DLLM_COPY(t_, stage_, slot_)                                                             \
+    do {                                                                                         \
+        const char *b_ = ((wave + NW * (t_)) < A_NI ? Ab : Wb) + (size_t)(stage_) * (BK * 2);    \
+        async_load16(b_, goff[t_], lds0 + (slot_) * (STAGE * 16) + (t_) * (NW * 1024));          \
     } while (0)
 
     floatx16 acc[TM][TN];
@@ -288,53 +327,78 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dl_kernel(const uint16_t *_
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    int a_row[TM], b_row[TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) a_row[i] = (wm * WTM + i * 32 + l32) * kChunksPerRow;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) b_row[j] = w_frag_row<BM, BN, WTN, TN, EPI>(j, wn, l32) * kChunksPerRow;
-    const int sw = (l32 >> 1) & 7;
+    const int sw = BK == 64 ? ((l32 >> 1) & 7) : ((l32 >> 2) & 3);
+    const int a_base = (wm * WTM + l32) * CPR, b_base = (BM + wn * WTN + l32) * CPR;  // uint4 index of fragment 0's row
+    bf16x8 af[2][TM], bfr[2][TN];
+    // fragments are read in the order of their first use by the MFMA sequence (i outer, j inner):
+    // A0, W0 .. W(TN-1), A1 .. A(TM-1)
+#define DLLM_READ(ridx_, st_, ch_, buf_)                                                                  \
+    do {                                                                                                  \
+        if ((ridx_) == 0) af[buf_][0] = as_bf16x8((st_)[a_base + (ch_)]);                                 \
+        else if ((ridx_) <= TN) bfr[buf_][((ridx_) - 1) % TN] = as_bf16x8((st_)[b_base + ((ridx_) - 1) * 32 * CPR + (ch_)]); \
+        else af[buf_][((ridx_) - TN) % TM] = as_bf16x8((st_)[a_base + ((ridx_) - TN) * 32 * CPR + (ch_)]); \
+    } while (0)
+
+    // every kernel argument the epilogue needs is in registers before the loop (see the file header)
+    asm volatile("" ::"s"(Cout), "s"(M), "s"(N), "s"(rope.table), "s"(rope.L), "s"(rope.rope_cols));
 
 #pragma unroll
-    for (int s = 0; s < NST - 1; ++s)
-        if (s < nk) DLLM_ISSUE_STAGE(s, s);
+    for (int s = 0; s < P; ++s)
+        if (s < nk) {
+#pragma unroll
+            for (int t = 0; t < LOADS; ++t) DLLM_COPY(t, s, s);
+        }
+    wait_stages_after<P - 1, LOADS>(min(P, nk) - 1);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int r = 0; r < NRD; ++r) DLLM_READ(r, smem, lhalf ^ sw, 0);
 
-    for (int kt = 0; kt < nk; ++kt) {
-        // step kt has landed once only the copies issued after it are outstanding
-        const int ahead = min(NST - 2, nk - 1 - kt);
-        if (NST >= 4 && ahead >= 2) wait_vmcnt<2 * LOADS>();
-        else if (NST >= 3 && ahead >= 1) wait_vmcnt<LOADS>();
-        else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();  // also: every wave is done reading the stage refilled below
-        asm volatile("" ::: "memory");
-        if (kt + NST - 1 < nk) DLLM_ISSUE_STAGE(kt + NST - 1, (kt + NST - 1) % NST);
-        const uint4 *st = smem + (kt % NST) * STAGE;
-        bf16x8 af[2][TM], bfr[2][TN];
+    int slot = 0, cslot = P % NST;  // slot of stage kt; slot that receives stage kt + P
+    int kt = 0;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[0][i] = as_bf16x8(st[a_row[i] + (lhalf ^ sw)]);
+    for (int phase = 0; phase < 2; ++phase) {
+        // phase 0: steady state, every step also copies stage kt + P; phase 1: the last P steps
+        const int kt_end = phase == 0 ? max(0, nk - P) : nk;
+        for (; kt < kt_end; ++kt) {
+            const int next_slot = slot + 1 == NST ? 0 : slot + 1;
+            const uint4 *st = smem + slot * STAGE, *stn = smem + next_slot * STAGE;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[0][j] = as_bf16x8(st[b_row[j] + (lhalf ^ sw)]);
+            for (int kk = 0; kk < KS; ++kk) {
+                const int cur = kk & 1, nxt = cur ^ 1;
+                const bool last = kk == KS - 1;
+                const uint4 *rs = last ? stn : st;
+                const int ch = last ? (lhalf ^ sw) : (((kk + 1) * 2 + lhalf) ^ sw);
+                if (last) {
+                    // every read of this stage has returned; stage kt+1 has landed for this wave, and
+                    // after the barrier for all of them; the slot of stage kt-1 was free a step ago
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    if (phase == 0) wait_vmcnt<(P - 2) * LOADS + (KS - 1) * LOADS / KS>();
+                    else wait_stages_after<P - 2, LOADS>(nk - 2 - kt);
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                }
+                const int c0 = kk * LOADS / KS, c1 = (kk + 1) * LOADS / KS, NC = c1 - c0;
 #pragma unroll
-        for (int kk = 0; kk < kBK / 16; ++kk) {
-            const int cur = kk & 1, nxt = cur ^ 1;
-            if (kk + 1 < kBK / 16) {
-                const int ch = ((kk + 1) * 2 + lhalf) ^ sw;
+                for (int m = 0; m < NMF; ++m) {
 #pragma unroll
-                for (int i = 0; i < TM; ++i) af[nxt][i] = as_bf16x8(st[a_row[i] + ch]);
+                    for (int r = m * NRD / NMF; r < (m + 1) * NRD / NMF; ++r) DLLM_READ(r, rs, ch, nxt);
+                    if (phase == 0) {
 #pragma unroll
-                for (int j = 0; j < TN; ++j) bfr[nxt][j] = as_bf16x8(st[b_row[j] + ch]);
+                        for (int c = c0 + m * NC / NMF; c < c0 + (m + 1) * NC / NMF; ++c) DLLM_COPY(c, kt + P, cslot);
+                    }
+                    acc[m / TN][m % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][m % TN], af[cur][m / TN],
+                                                                                 acc[m / TN][m % TN], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);  // keeps the hand-made interleaving
+                }
             }
-            __builtin_amdgcn_sched_barrier(0);  // next fragments are requested before this substep's MFMAs
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+            slot = next_slot;
+            cslot = cslot + 1 == NST ? 0 : cslot + 1;
         }
     }
-#undef DLLM_ISSUE_STAGE
-    store_tile<TM, TN, WTM, WTN, EPI>(acc, Cout, M, N, n_out, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
+#undef DLLM_COPY
+#undef DLLM_READ
+    store_tile<TM, TN, WTM, EPI>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
 }
 
 // ---- fallback kernel: any K % 8 == 0 -------------------------------------------
@@ -344,9 +408,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *
                                                             int M, int N, int K, int k_per_split, int num_m, int num_n,
                                                             RopeArgs rope)
 {
+    constexpr int kBK = 64, kChunksPerRow = 8;
     constexpr int kThreads = WM * WN * 64, RPL = kThreads / kChunksPerRow;  // rows covered by one load of all threads
     constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
-    static_assert(EPI != kEpiSwiglu || (TN % 2 == 0), "SwiGLU pairs gate/up sub-tiles");
     constexpr int ROWS = BM + BN;
     constexpr int LOADS = ROWS / RPL;
     constexpr int A_LOADS = BM / RPL;
@@ -356,9 +420,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *
 
     int pid_m, pid_n;
     tile_of(blockIdx.x, num_m, num_n, pid_m, pid_n);
-    constexpr int BN_OUT = (EPI == kEpiSwiglu) ? BN / 2 : BN;
+    constexpr int BN_OUT = epi_paired(EPI) ? BN / 2 : BN;
     const int m0 = pid_m * BM, n0 = pid_n * BN_OUT;
-    const int n_out = (EPI == kEpiSwiglu) ? N / 2 : N;
+    const int n_lim = epi_paired(EPI) ? N / 2 : N;  // columns or pairs of the matrix
     const int kbeg = blockIdx.y * k_per_split;
     const int kend = min(K, kbeg + k_per_split);
     const int nk = (kend - kbeg + kBK - 1) / kBK;
@@ -377,13 +441,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *
         if (t < A_LOADS) {
             ok[t] = m0 + r < M;
             grow = m0 + r;
-        } else if (EPI == kEpiSwiglu) {
-            const int j = r - BM, half = j / (BN / 2), jj = j % (BN / 2);
-            ok[t] = n0 + jj < n_out;
-            grow = half * n_out + n0 + jj;
         } else {
-            ok[t] = n0 + r - BM < N;
-            grow = n0 + r - BM;
+            const int j = r - BM;
+            ok[t] = epi_paired(EPI) ? (n0 + (j >> 5) * 16 + (j & 15) < n_lim) : (n0 + j < n_lim);
+            grow = w_global_row<EPI>(j, n0, N);
         }
         src[t] = (t < A_LOADS ? A : W) + (size_t)(ok[t] ? grow : 0) * K + ld_kc * 8;
     }
@@ -400,7 +461,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *
 #pragma unroll
     for (int i = 0; i < TM; ++i) a_row[i] = (wm * WTM + i * 32 + l32) * kChunksPerRow;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) b_row[j] = w_frag_row<BM, BN, WTN, TN, EPI>(j, wn, l32) * kChunksPerRow;
+    for (int j = 0; j < TN; ++j) b_row[j] = (BM + wn * WTN + j * 32 + l32) * kChunksPerRow;
     const int sw = (l32 >> 1) & 7;
 
     for (int kt = 0; kt <= nk; ++kt) {
@@ -438,30 +499,28 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
     }
-    store_tile<TM, TN, WTM, WTN, EPI>(acc, Cout, M, N, n_out, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
+    store_tile<TM, TN, WTM, EPI>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
 }
 
 // ---- host side ----------------------------------------------------------------
 
-// Tile shapes with the cost of one K-step and of the epilogue in shader clocks,
-// measured on MI355X at M = 512 (copy and math of a step overlap only partly:
-// the LDS port is shared by the asynchronous copies and the fragment reads).
+// Tile shapes with the modelled cost of one 64-deep K-step and of the epilogue in
+// microseconds when every CU holds a workgroup (measured on MI355X at M = 512 with
+// random operands; under that load the shader clock sits near 1.5 GHz).
 struct TileCfg {
-    int bm, bn, nst, waves;
-    float step_clk, epi_clk;
+    int bm, bn, bk, nst, waves;
+    float step_us, epi_us;
 };
-constexpr int kNumCfg = 7;
+constexpr int kNumCfg = 6;
 const TileCfg kCfg[kNumCfg] = {
-    {256, 256, 2, 8, 3180.f, 24000.f}, {256, 192, 2, 8, 2670.f, 18000.f}, {256, 128, 3, 8, 1730.f, 11800.f},
-    {256, 128, 3, 8, 1880.f, 11800.f}, {256, 96, 3, 4, 1950.f, 8900.f},   {128, 128, 3, 8, 1175.f, 5800.f},
-    {128, 64, 4, 4, 800.f, 3000.f},
+    {256, 256, 32, 4, 4, 1.85f, 9.0f}, {256, 192, 32, 5, 4, 1.40f, 8.0f}, {256, 128, 64, 3, 4, 0.88f, 6.0f},
+    {256, 96, 64, 3, 4, 0.77f, 5.0f},  {128, 128, 64, 4, 4, 0.62f, 3.5f}, {128, 64, 64, 4, 4, 0.40f, 2.5f},
 };
 constexpr int kNumCU = 256;
-constexpr int kLdsPerCU = 160 * 1024;
 
 struct Plan {
     int cfg, splits;
-    bool fast;  // gemm_dl_kernel
+    bool fast;  // gemm_il_kernel
 };
 
 int env_int(const char *name, int dflt)
@@ -470,25 +529,28 @@ int env_int(const char *name, int dflt)
     return s ? atoi(s) : dflt;
 }
 
-bool cfg_allows(int c, GemmEpilogue epi, bool fast)
+// epi: a GemmEpilogue value or one of the rotary epilogues
+bool cfg_allows(int c, int epi, bool fast)
 {
-    if (epi == kEpiSwiglu && c == 4) return false;   // 256x96 as 4x1 waves: odd number of sub-tiles per wave
-    if (epi == kEpiPartial && c == 0) return false;  // 256x256 fp32 epilogue runs out of registers
-    if (!fast && c < 2) return false;                // the register-staged kernel keeps to the smaller tiles
-    if (epi != kEpiPartial && c == 3) return false;  // 256x128 as 8x1 waves only pays off for the split-K shapes
+    if (!fast && c < 2) return false;  // the register-staged kernel keeps to the smaller tiles
+    // 256 accumulator registers per lane leave no room for the fp32 and the rotary epilogue
+    if (c == 0 && (epi == kEpiPartial || epi == kEpiRope64 || epi == kEpiRope128)) return false;
     return true;
 }
 
 // Lowest modelled time: rounds of workgroups over the CUs, each round costing
 // the K-steps of one tile plus its epilogue, plus the traffic of the fp32 slabs.
-Plan make_plan(GemmEpilogue epi, int M, int N, int K)
+Plan make_plan(int epi, int M, int N, int K)
 {
     const int n_out = epi == kEpiSwiglu ? N / 2 : N;
     // the asynchronous-copy kernel needs whole K-steps and 32-bit byte offsets
-    const bool fast = (K % kBK == 0) && ((double)M * K * 2 < 4.0e9) && ((double)N * K * 2 < 4.0e9) &&
+    const bool fast = (K % 64 == 0) && ((double)M * K * 2 < 4.0e9) && ((double)N * K * 2 < 4.0e9) &&
                       env_int("DLLM_GEMM_FALLBACK", 0) == 0;
-    const int fc = env_int("DLLM_GEMM_CFG", -1), fs = env_int("DLLM_GEMM_SPLITS", -1);
-    Plan best{5, 1, fast};
+    // test and tuning hooks: DLLM_GEMM_CFG forces a tile shape for every product, DLLM_GEMM_CFG_E<epilogue> for one epilogue
+    char per_epi[32];
+    snprintf(per_epi, sizeof per_epi, "DLLM_GEMM_CFG_E%d", epi);
+    const int fc = env_int(per_epi, env_int("DLLM_GEMM_CFG", -1)), fs = env_int("DLLM_GEMM_SPLITS", -1);
+    Plan best{4, 1, fast};
     double best_cost = 1e300;
     const int max_splits = epi == kEpiPartial ? 8 : 1;
     for (int c = 0; c < kNumCfg; ++c) {
@@ -496,33 +558,34 @@ Plan make_plan(GemmEpilogue epi, int M, int N, int K)
         const TileCfg &t = kCfg[c];
         const int bn_out = epi == kEpiSwiglu ? t.bn / 2 : t.bn;
         const long tiles = (long)((M + t.bm - 1) / t.bm) * ((n_out + bn_out - 1) / bn_out);
-        const int per_cu = kLdsPerCU / ((fast ? t.nst : 2) * (t.bm + t.bn) * 128) >= 2 ? 2 : 1;
         for (int s = 1; s <= max_splits; ++s) {
             if (fs >= 1 && fs <= max_splits && s != fs) continue;
-            const int kps = ((K + s - 1) / s + kBK - 1) / kBK * kBK;
-            if (s > 1 && (long)kps * (s - 1) >= K) continue;   // the last split would be empty
+            const int kps = ((K + s - 1) / s + 63) / 64 * 64;
+            if (s > 1 && (long)kps * (s - 1) >= K) continue;  // the last split would be empty
             const long wgs = tiles * s;
-            const long rounds = (wgs + (long)kNumCU * per_cu - 1) / ((long)kNumCU * per_cu);
-            double cost = (double)rounds * per_cu * ((double)(kps / kBK) * t.step_clk + t.epi_clk + 2500.0);
-            if (epi == kEpiPartial) cost += (double)s * M * N * 8.0 / (4000.0 / 2.4);  // slab write + read, ~4 TB/s
+            const long rounds = (wgs + kNumCU - 1) / kNumCU;
+            // a round that leaves CUs idle runs its workgroups faster (power and bandwidth are shared by fewer)
+            const double fill = (double)wgs / (double)(rounds * kNumCU);
+            double cost = (double)rounds * ((double)(kps / 64) * t.step_us * (0.55 + 0.45 * fill) + t.epi_us + 1.5);
+            if (epi == kEpiPartial) cost += (double)s * M * N * 8.0 / 4.0e6;  // slab write + read, ~4 TB/s
             if (cost < best_cost) { best_cost = cost; best = Plan{c, s, fast}; }
         }
     }
     return best;
 }
 
-template <int BM, int BN, int WM, int WN, int NST, int EPI>
+template <int BM, int BN, int WM, int WN, int BK, int NST, int EPI>
 hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *W, void *C, int M, int N, int K,
-                      int splits, RopeArgs rope = RopeArgs{nullptr, 1, 64, 0})
+                      int splits, RopeArgs rope = RopeArgs{nullptr, 1, 0})
 {
-    constexpr int BN_OUT = EPI == kEpiSwiglu ? BN / 2 : BN;
-    const int n_out = EPI == kEpiSwiglu ? N / 2 : N;
-    const int num_m = (M + BM - 1) / BM, num_n = (n_out + BN_OUT - 1) / BN_OUT;
-    const int kps = ((K + splits - 1) / splits + kBK - 1) / kBK * kBK;
+    constexpr int BN_OUT = epi_paired(EPI) ? BN / 2 : BN;
+    const int n_lim = epi_paired(EPI) ? N / 2 : N;
+    const int num_m = (M + BM - 1) / BM, num_n = (n_lim + BN_OUT - 1) / BN_OUT;
+    const int kps = ((K + splits - 1) / splits + 63) / 64 * 64;
     const dim3 grid(num_m * num_n, splits), block(WM * WN * 64);
     if (fast) {
-        const size_t lds = (size_t)NST * (BM + BN) * kChunksPerRow * sizeof(uint4);
-        auto kern = gemm_dl_kernel<BM, BN, WM, WN, NST, EPI>;
+        const size_t lds = (size_t)NST * (BM + BN) * BK * 2;
+        auto kern = gemm_il_kernel<BM, BN, WM, WN, BK, NST, EPI>;
         static bool attr_done = false;
         if (!attr_done) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -532,8 +595,10 @@ hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *
         }
         hipLaunchKernelGGL(kern, grid, block, lds, stream, (const uint16_t *)A, (const uint16_t *)W, C, M, N, K, kps,
                            num_m, num_n, rope);
+    } else if constexpr (BM * BN > 256 * 128) {
+        return hipErrorInvalidValue;  // never planned: see cfg_allows
     } else {
-        const size_t lds = (size_t)2 * (BM + BN) * kChunksPerRow * sizeof(uint4);
+        const size_t lds = (size_t)2 * (BM + BN) * 128;
         auto kern = gemm_reg_kernel<BM, BN, WM, WN, EPI>;
         static bool attr_done = false;
         if (!attr_done) {
@@ -549,18 +614,19 @@ hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *
 }
 
 template <int EPI>
-hipError_t dispatch(hipStream_t stream, Plan p, const void *A, const void *W, void *C, int M, int N, int K)
+hipError_t dispatch(hipStream_t stream, Plan p, const void *A, const void *W, void *C, int M, int N, int K,
+                    RopeArgs rope = RopeArgs{nullptr, 1, 0})
 {
     switch (p.cfg) {
-    case 0: return launch_cfg<256, 256, 4, 2, 2, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
-    case 1: return launch_cfg<256, 192, 8, 1, 2, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
-    case 2: return launch_cfg<256, 128, 4, 2, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
-    case 3: return launch_cfg<256, 128, 8, 1, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
-    case 4:
-        if constexpr (EPI != kEpiSwiglu) return launch_cfg<256, 96, 4, 1, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
-        return hipErrorInvalidValue;
-    case 5: return launch_cfg<128, 128, 4, 2, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
-    default: return launch_cfg<128, 64, 4, 1, 4, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits);
+    case 0:
+        if constexpr (EPI == kEpiBf16 || EPI == kEpiSwiglu)
+            return launch_cfg<256, 256, 2, 2, 32, 4, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
+        return hipErrorInvalidValue;  // never planned: see cfg_allows
+    case 1: return launch_cfg<256, 192, 2, 2, 32, 5, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
+    case 2: return launch_cfg<256, 128, 2, 2, 64, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
+    case 3: return launch_cfg<256, 96, 4, 1, 64, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
+    case 4: return launch_cfg<128, 128, 2, 2, 64, 4, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
+    default: return launch_cfg<128, 64, 2, 2, 64, 4, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
     }
 }
 
@@ -570,18 +636,18 @@ int gemm_num_splits(int M, int N, int K) { return make_plan(kEpiPartial, M, N, K
 
 bool gemm_qkv_rope_supported(int M, int d, int dh)
 {
-    // whole heads per 128-column tile, q/k boundary on a tile edge, asynchronous-copy kernel
-    return (dh == 64 || dh == 128) && d % 128 == 0 && d % kBK == 0 && (double)M * d * 2 < 4.0e9 &&
+    // pairs (c, c + dh/2) in groups of 16 inside one head; the q/k boundary on a head edge; asynchronous-copy kernel
+    return (dh == 64 || dh == 128) && d % dh == 0 && d % 64 == 0 && (double)M * d * 2 < 4.0e9 &&
            (double)3 * d * d * 2 < 4.0e9 && env_int("DLLM_GEMM_FALLBACK", 0) == 0 && env_int("DLLM_NO_FUSED_ROPE", 0) == 0;
 }
 
 hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
                                 const float2 *table, int L)
 {
-    // 256x128 tile as 8x1 waves: a wave owns 32 rows x 128 columns = whole heads
-    const RopeArgs rope{table, L, dh, 2 * d};
-    if (dh == 128) return launch_cfg<256, 128, 8, 1, 3, kEpiRope128>(stream, true, A, W, C, M, 3 * d, d, 1, rope);
-    return launch_cfg<256, 128, 8, 1, 3, kEpiRope64>(stream, true, A, W, C, M, 3 * d, d, 1, rope);
+    const RopeArgs rope{table, L, 2 * d};
+    const Plan p = make_plan(dh == 128 ? kEpiRope128 : kEpiRope64, M, 3 * d, d);
+    if (dh == 128) return dispatch<kEpiRope128>(stream, p, A, W, C, M, 3 * d, d, rope);
+    return dispatch<kEpiRope64>(stream, p, A, W, C, M, 3 * d, d, rope);
 }
 
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
