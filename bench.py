@@ -190,7 +190,7 @@ def main():
                    "global_batch": B, "seq_len": L},
         "step_tflops": flops / 1e12,
         "step_mfma_frac": flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "roofline": {"kernel": "gemm_dl_kernel<256,192,8 waves,SwiGLU> (gate/up projection, one launch per layer)",
+        "roofline": {"kernel": "gemm_il_kernel<256,192,2x2 waves,BK 32,5 stages,SwiGLU> (gate/up projection, one launch per layer)",
                      "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
                      "avg_launch_ms": k_avg_ms, "launches": k_launches, "flops_per_launch": k_flops},

@@ -69,11 +69,27 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__r
 
     const int d = H * DH;
     const size_t ld = (size_t)3 * d;
-    const int h = blockIdx.y, b = blockIdx.z;
+    // Workgroups of one (batch, head) share its K and V: give them ids congruent mod 8, which
+    // the dispatcher places on the same XCD, so each K/V tile crosses into one L2 only.
+    const int nq = (L + QT - 1) / QT, nbh = (int)gridDim.x / nq;
+    int qblk, bh;
+    {
+        const int pid = blockIdx.x, n8 = nbh & ~7, head = nq * n8;
+        if (pid < head) {
+            const int j = pid >> 3;
+            qblk = j % nq;
+            bh = (j / nq) * 8 + (pid & 7);
+        } else {
+            const int r = pid - head;
+            qblk = r % nq;
+            bh = n8 + r / nq;
+        }
+    }
+    const int h = bh % H, b = bh / H;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int half = KVSPLIT == 2 ? wave >> 1 : 0, qgroup = KVSPLIT == 2 ? wave & 1 : wave, htid = tid & (HT - 1);
     const int l32 = lane & 31, g = lane >> 5;
-    const int q0 = blockIdx.x * QT + qgroup * 32;
+    const int q0 = qblk * QT + qgroup * 32;
     const uint16_t *base = qkv + (size_t)b * L * ld;
     const float c = kLog2e / sqrtf((float)DH);
 
@@ -302,7 +318,7 @@ hipError_t launch_split(hipStream_t stream, const void *qkv, void *out, int B, i
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((L + QT - 1) / QT, H, B), dim3(kThreads), lds, stream, (const uint16_t *)qkv,
+    hipLaunchKernelGGL(kern, dim3(((L + QT - 1) / QT) * H * B), dim3(kThreads), lds, stream, (const uint16_t *)qkv,
                        (uint16_t *)out, L, H);
     return hipGetLastError();
 }
