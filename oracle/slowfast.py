@@ -229,3 +229,57 @@ def decode(predict: Predictor, tokens, mask, gen_start: int, gen_end: int, p: De
                 ctl[b].observe(res[b][3], res[b][4], mask[b])
         if trace is not None:
             trace.append((sps, res))
+
+
+def n_unmasked_target(length: int, n_steps: int, j: int) -> int:
+    """Low-confidence remasking schedule (Section 2.1): after the j-th of n_steps
+    steps (the paper's k = n_steps - j + 1, t_{k-1} = (k - 1) / n_steps) the state
+    holds floor(length * (1 - t_{k-1})) = floor(length * j / n_steps) unmasked tokens."""
+    return (length * j) // n_steps
+
+
+def decode_low_confidence(predict: Predictor, tokens, mask, gen_start: int, gen_end: int, n_steps: int,
+                          block_len: Optional[int] = None, trace: Optional[list] = None) -> int:
+    """The baseline sampler the paper starts from (Section 2.1): low-confidence
+    remasking, optionally semi-autoregressive over blocks of block_len positions
+    that are denoised left to right with n_steps / n_blocks steps each.
+
+    Every step predicts all masked positions of the current block; committed
+    positions have confidence 1 and stay, so "keep the n_un most confident" means:
+    unmask the (n_un - already unmasked) most confident masked positions of the
+    block (ties: lower position).  A step whose target is already met commits
+    nothing and is skipped without a forward pass.  Returns the forward passes run."""
+    B, L = tokens.shape
+    G = gen_end - gen_start
+    block_len = G if block_len is None else block_len
+    if G <= 0:
+        return 0
+    if block_len < 1 or G % block_len:
+        raise ValueError("block_len must divide the generated length")
+    n_blocks = G // block_len
+    if n_steps < n_blocks or n_steps % n_blocks:
+        raise ValueError("n_steps must be a positive multiple of the number of blocks")
+    per_block = n_steps // n_blocks
+    prev_pred = np.full((B, L), -1, dtype=np.int32)
+    steps = 0
+    for blk in range(n_blocks):
+        lo = gen_start + blk * block_len
+        hi = lo + block_len                      # exclusive
+        for j in range(1, per_block + 1):
+            target = n_unmasked_target(block_len, per_block, j)
+            sps = []
+            for b in range(B):
+                unmasked = block_len - int(mask[b, lo:hi].sum())
+                k = target - unmasked
+                if k >= 1:
+                    # the slow-stage rule on the window [lo, hi): top-k by confidence
+                    sps.append(StageParams(SLOW, lo, hi - 1, k, 0.0, 1.0, 0, gen_start, hi))
+                else:
+                    sps.append(StageParams(IDLE, 0, -1, 1, 0.0, 1.0, 0, gen_start, hi))
+            if all(sp.stage == IDLE for sp in sps):
+                continue
+            res = step(predict, tokens, mask, prev_pred, sps)
+            steps += 1
+            if trace is not None:
+                trace.append((sps, res))
+    return steps

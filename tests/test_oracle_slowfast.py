@@ -235,3 +235,83 @@ def test_max_steps_stops_the_decode():
     p = sf.DecodeParams(max_steps=3)
     assert sf.decode(fixed_conf_predictor(conf, pred), tokens, mask, P, L, p) == 3
     assert mask.sum() == L - P - 3
+
+
+# ---- low-confidence remasking baseline (Section 2.1) ------------------------------
+
+def test_low_confidence_schedule_values():
+    # n_un = floor(L (1 - (k-1)/N)), k = N .. 1, worked by hand:
+    # L = 10, N = 4: 10*1/4 = 2.5, 10*2/4 = 5, 10*3/4 = 7.5, 10 -> 2, 5, 7, 10
+    assert [sf.n_unmasked_target(10, 4, j) for j in (1, 2, 3, 4)] == [2, 5, 7, 10]
+    # L = N: one more token per step;  L = 7, N = 3: 2.33, 4.67, 7 -> 2, 4, 7
+    assert [sf.n_unmasked_target(6, 6, j) for j in range(1, 7)] == [1, 2, 3, 4, 5, 6]
+    assert [sf.n_unmasked_target(7, 3, j) for j in (1, 2, 3)] == [2, 4, 7]
+
+
+def test_low_confidence_decode_commits_in_order_of_confidence():
+    rng = np.random.default_rng(8)
+    P, G = 2, 10
+    L = P + G
+    conf = rng.random((1, L)).astype(np.float32)
+    pred = rng.integers(0, 50, (1, L)).astype(np.int32)
+    ranked = sorted(range(P, L), key=lambda i: -conf[0, i])
+    for n_steps, sizes in ((10, [1] * 10), (4, [2, 3, 2, 3]), (1, [10])):
+        tokens = np.full((1, L), 99, np.int32); mask = np.zeros((1, L), np.uint8); mask[:, P:] = 1
+        trace = []
+        steps = sf.decode_low_confidence(fixed_conf_predictor(conf, pred), tokens, mask, P, L, n_steps, None, trace)
+        assert steps == n_steps
+        got = [res[0][0] for _, res in trace]
+        assert [len(c) for c in got] == sizes
+        at = 0
+        for c in got:                                  # each step takes the next most confident ones
+            assert sorted(c) == sorted(ranked[at:at + len(c)])
+            at += len(c)
+        assert not mask.any() and np.array_equal(tokens[0, P:], pred[0, P:])
+
+
+def test_low_confidence_decode_equals_the_slowfast_special_case():
+    # N = G: the reduction used by test_reduces_to_low_confidence_remasking must give the same trajectory
+    rng = np.random.default_rng(9)
+    P, G = 1, 12
+    L = P + G
+    conf = rng.random((2, L)).astype(np.float32)
+    pred = rng.integers(0, 50, (2, L)).astype(np.int32)
+    t1 = np.full((2, L), 99, np.int32); m1 = np.zeros((2, L), np.uint8); m1[:, P:] = 1
+    t2, m2 = t1.copy(), m1.copy()
+    tr1, tr2 = [], []
+    sf.decode_low_confidence(fixed_conf_predictor(conf, pred), t1, m1, P, L, G, None, tr1)
+    p = sf.DecodeParams(max_steps=1000, tau_min_conf=-1.0, tau_high_conf=1.0, k_slow=1, k_fast=1)
+    sf.decode(fixed_conf_predictor(conf, pred), t2, m2, P, L, p, tr2)
+    assert [[r[0] for r in res] for _, res in tr1] == [[r[0] for r in res] for _, res in tr2]
+    assert np.array_equal(t1, t2)
+
+
+def test_semi_autoregressive_blocks_go_left_to_right():
+    P, G, Lb = 3, 12, 4
+    L = P + G
+    conf = np.linspace(0.1, 0.9, L, dtype=np.float32)[None]       # rightmost is the most confident
+    pred = np.arange(L, dtype=np.int32)[None]
+    tokens = np.full((1, L), 99, np.int32); mask = np.zeros((1, L), np.uint8); mask[:, P:] = 1
+    trace = []
+    steps = sf.decode_low_confidence(fixed_conf_predictor(conf, pred), tokens, mask, P, L, 6, Lb, trace)
+    assert steps == 6                                              # 3 blocks x 2 steps x 2 tokens
+    got = [res[0][0] for _, res in trace]
+    assert got == [[5, 6], [3, 4], [9, 10], [7, 8], [13, 14], [11, 12]]
+    with pytest.raises(ValueError):
+        sf.decode_low_confidence(fixed_conf_predictor(conf, pred), tokens, mask, P, L, 6, 5)
+    with pytest.raises(ValueError):
+        sf.decode_low_confidence(fixed_conf_predictor(conf, pred), tokens, mask, P, L, 4, Lb)
+
+
+def test_low_confidence_decode_skips_steps_whose_target_is_met():
+    # half of the region is already unmasked: the first steps have nothing to add and run no forward
+    P, G = 0, 8
+    conf = np.linspace(0.9, 0.1, G, dtype=np.float32)[None]
+    pred = np.arange(G, dtype=np.int32)[None]
+    tokens = np.full((1, G), 99, np.int32); mask = np.ones((1, G), np.uint8); mask[0, :4] = 0
+    calls = []
+    def predict(tokens, active):
+        calls.append(1)
+        return pred.copy(), np.where(active == 1, conf, 0).astype(np.float32)
+    steps = sf.decode_low_confidence(predict, tokens, mask, P, G, 8, None)
+    assert steps == 4 == len(calls) and not mask.any()
