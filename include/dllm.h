@@ -172,6 +172,22 @@ int dllm_step(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *ma
 int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t *tokens, uint8_t *mask,
                 const dllm_decode_params *p, int32_t *steps_taken, dllm_step_stat *stats, int32_t stats_capacity);
 
+/* The baseline sampler the method is measured against (Section 2.1, "Low-Confidence
+ * Remasking", optionally "Semi-Autoregressive"): the generated region [gen_start, L) is
+ * cut into blocks of block_len positions that are denoised left to right with
+ * n_steps / (number of blocks) steps each; after the j-th of a block's N_b steps the
+ * block holds floor(block_len * j / N_b) unmasked tokens, the newly unmasked ones being
+ * the most confident masked positions of the block (ties: lower position).  A step
+ * whose target a sequence already meets commits nothing there; a step no sequence
+ * needs runs no forward pass.  Uses the same step kernels as dllm_decode (the
+ * slow-stage rule with top_k from the schedule and the block as window).
+ *   block_len   <= 0 means one block over the whole region; must divide L - gen_start
+ *   n_steps     a positive multiple of the number of blocks
+ * Other arguments, synchronisation and errors as dllm_decode. */
+int dllm_decode_low_confidence(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t *tokens,
+                               uint8_t *mask, int32_t n_steps, int32_t block_len, int32_t *steps_taken,
+                               dllm_step_stat *stats, int32_t stats_capacity);
+
 /* Test and measurement hooks: device pointers into the workspace, valid until
  * the next call on the handle.  logits: bf16 [B*L][vocab] of the last forward
  * (after dllm_step only the rows inside each sequence's window are defined:

@@ -60,7 +60,7 @@ class StepStat(C.Structure):
                 ("ms", C.c_float)]
 
 
-EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_decode", "dllm_debug_logits",
+EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_decode", "dllm_decode_low_confidence", "dllm_debug_logits",
            "dllm_debug_rows", "dllm_profile_begin", "dllm_profile_end", "dllm_forward", "dllm_select", "dllm_op_linear", "dllm_op_linear_swiglu",
            "dllm_op_add_rmsnorm", "dllm_op_rope", "dllm_op_linear_qkv_rope", "dllm_op_attention"]
 
@@ -212,6 +212,19 @@ class Model:
         stats = (StepStat * max(stats_capacity, 1))()
         _check(lib().dllm_decode(self._h, B, L, gen_start, _ptr(tokens), _ptr(mask), C.byref(params),
                                  C.byref(steps), stats if stats_capacity else None, stats_capacity), self._h)
+        n = min(steps.value, stats_capacity)
+        return steps.value, [(s.n_slow, s.n_fast, s.n_idle, s.n_commit, s.ms) for s in stats[:n]]
+
+
+    def decode_low_confidence(self, tokens, mask, gen_start: int, n_steps: int, block_len: int = 0,
+                              stats_capacity: int = 0):
+        _dev(tokens, torch.int32, "tokens"); _dev(mask, torch.uint8, "mask")
+        B, L = tokens.shape
+        steps = C.c_int32(0)
+        stats = (StepStat * max(stats_capacity, 1))()
+        _check(lib().dllm_decode_low_confidence(self._h, B, L, gen_start, _ptr(tokens), _ptr(mask), n_steps, block_len,
+                                                C.byref(steps), stats if stats_capacity else None, stats_capacity),
+               self._h)
         n = min(steps.value, stats_capacity)
         return steps.value, [(s.n_slow, s.n_fast, s.n_idle, s.n_commit, s.ms) for s in stats[:n]]
 

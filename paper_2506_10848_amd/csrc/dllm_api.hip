@@ -478,6 +478,85 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
     return DLLM_OK;
 }
 
+int dllm_decode_low_confidence(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t *tokens,
+                               uint8_t *mask, int32_t n_steps, int32_t block_len, int32_t *steps_taken,
+                               dllm_step_stat *stats, int32_t stats_capacity)
+{
+    int rc = check_batch(h, B, L);
+    if (rc) return rc;
+    if (!tokens || !mask || !steps_taken) return fail(h, DLLM_EINVAL, "dllm_decode_low_confidence: null argument");
+    if (gen_start < 0 || gen_start > L)
+        return fail(h, DLLM_EINVAL, "dllm_decode_low_confidence: gen_start %d outside [0, %d]", gen_start, L);
+    if (stats && stats_capacity < 0) return fail(h, DLLM_EINVAL, "dllm_decode_low_confidence: negative stats_capacity");
+    const int G = L - gen_start;
+    *steps_taken = 0;
+    if (G == 0) return DLLM_OK;
+    const int lb = block_len <= 0 ? G : block_len;
+    if (G % lb) return fail(h, DLLM_EINVAL, "dllm_decode_low_confidence: block_len %d does not divide the %d generated positions", lb, G);
+    const int n_blocks = G / lb;
+    if (n_steps < n_blocks || n_steps % n_blocks)
+        return fail(h, DLLM_EINVAL, "dllm_decode_low_confidence: n_steps %d is not a positive multiple of the %d blocks", n_steps, n_blocks);
+    const int per_block = n_steps / n_blocks;
+
+    Workspace &w = h->ws;
+    const int mb = h->cfg.max_batch;
+    hipStream_t st = h->stream;
+    HIP_TRY(h, hipMemsetAsync(w.prev_pred, 0xff, (size_t)B * L * sizeof(int32_t), st));
+    uint8_t *hmask = w.host_pinned;
+    int32_t *hints = reinterpret_cast<int32_t *>(w.host_pinned + (((size_t)h->cfg.max_batch * h->cfg.max_seq + 63) & ~(size_t)63));
+    HIP_TRY(h, hipMemcpyAsync(hmask, mask, (size_t)B * L, hipMemcpyDeviceToHost, st));
+    HIP_TRY(h, hipStreamSynchronize(st));
+
+    dllm_commit_list cl;
+    cl.capacity = L;
+    cl.n_commit = w.cl_ints; cl.e_cand = w.cl_ints + mb; cl.first_masked = w.cl_ints + 2 * mb;
+    cl.n_masked_after = w.cl_ints + 3 * mb;
+    cl.pos = w.cl_pos; cl.tok = w.cl_tok; cl.conf = w.cl_conf;
+
+    std::vector<dllm_stage_params> sps(B);
+    int steps = 0;
+    for (int blk = 0; blk < n_blocks; ++blk) {
+        const int lo = gen_start + blk * lb, hi = lo + lb;  // [lo, hi)
+        for (int j = 1; j <= per_block; ++j) {
+            const long target = (long)lb * j / per_block;  // tokens of the block unmasked after this step
+            int n_live = 0;
+            for (int b = 0; b < B; ++b) {
+                int masked = 0;
+                for (int i = lo; i < hi; ++i) masked += hmask[(size_t)b * L + i] != 0;
+                const long k = target - (lb - masked);
+                dllm_stage_params &sp = sps[b];
+                sp.tau_min_conf = 0.0f; sp.tau_high_conf = 1.0f; sp.conv_mode = 0;
+                sp.gen_start = gen_start; sp.gen_end = hi;
+                if (k >= 1) {
+                    sp.stage = DLLM_STAGE_SLOW; sp.s_cycle = lo; sp.e_cycle = hi - 1; sp.top_k = (int)k;
+                    ++n_live;
+                } else {
+                    sp.stage = DLLM_STAGE_IDLE; sp.s_cycle = 0; sp.e_cycle = -1; sp.top_k = 1;
+                }
+            }
+            if (n_live == 0) continue;
+            const bool timed = stats && steps < stats_capacity;
+            if (timed) HIP_TRY(h, hipEventRecord(h->ev0, st));
+            if ((rc = dllm_step(h, B, L, tokens, mask, w.prev_pred, sps.data(), &cl))) return rc;
+            if (timed) HIP_TRY(h, hipEventRecord(h->ev1, st));
+            HIP_TRY(h, hipMemcpyAsync(hmask, mask, (size_t)B * L, hipMemcpyDeviceToHost, st));
+            HIP_TRY(h, hipMemcpyAsync(hints, w.cl_ints, (size_t)4 * mb * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+            HIP_TRY(h, hipStreamSynchronize(st));
+            if (timed) {
+                int committed = 0;
+                for (int b = 0; b < B; ++b)
+                    if (sps[b].stage != DLLM_STAGE_IDLE) committed += hints[b];
+                float ms = 0.0f;
+                HIP_TRY(h, hipEventElapsedTime(&ms, h->ev0, h->ev1));
+                stats[steps] = dllm_step_stat{n_live, 0, B - n_live, committed, ms};
+            }
+            ++steps;
+        }
+    }
+    *steps_taken = steps;
+    return DLLM_OK;
+}
+
 int dllm_profile_begin(dllm_handle *h, int32_t max_launches)
 {
     if (!h) return fail(nullptr, DLLM_EINVAL, "dllm_profile_begin: handle is null");

@@ -84,7 +84,58 @@ class Robust:
         return val, robust
 
 
-def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9):
+class SlowFastDriver:
+    """Stage parameters of every step from the oracle's Algorithm 1 controllers."""
+
+    def __init__(self, B, P, L, params):
+        self.ctl = [sf.Controller(P, L, params) for _ in range(B)]
+        self.P, self.L, self.p = P, L, params
+
+    def next(self, mask):
+        sps = []
+        for s, c in enumerate(self.ctl):
+            sp = c.next_params(mask[s])
+            sps.append(sp if sp is not None else
+                       sf.StageParams(sf.IDLE, 0, -1, 1, self.p.tau_min_conf, self.p.tau_high_conf, self.p.conv_mode,
+                                      self.P, self.L))
+        return sps
+
+    def observe(self, sps, res, mask):
+        for s, c in enumerate(self.ctl):
+            if sps[s].stage != sf.IDLE:
+                c.observe(res[s][3], res[s][4], mask[s])
+
+
+class LowConfidenceDriver:
+    """Stage parameters of the baseline sampler (Section 2.1): block by block, the
+    schedule's number of new tokens per step, taken from the oracle's schedule function."""
+
+    def __init__(self, B, P, L, n_steps, block_len):
+        G = L - P
+        self.blocks = [(P + i * block_len, P + (i + 1) * block_len) for i in range(G // block_len)]
+        self.per_block = n_steps // len(self.blocks)
+        self.plan = [(lo, hi, j) for lo, hi in self.blocks for j in range(1, self.per_block + 1)]
+        self.P, self.at = P, 0
+
+    def next(self, mask):
+        while self.at < len(self.plan):
+            lo, hi, j = self.plan[self.at]
+            self.at += 1
+            target = sf.n_unmasked_target(hi - lo, self.per_block, j)
+            sps = []
+            for s in range(mask.shape[0]):
+                k = target - ((hi - lo) - int(mask[s, lo:hi].sum()))
+                sps.append(sf.StageParams(sf.SLOW, lo, hi - 1, k, 0.0, 1.0, 0, self.P, hi) if k >= 1 else
+                           sf.StageParams(sf.IDLE, 0, -1, 1, 0.0, 1.0, 0, self.P, hi))
+            if any(sp.stage != sf.IDLE for sp in sps):
+                return sps
+        return [sf.StageParams(sf.IDLE, 0, -1, 1, 0.0, 1.0, 0, self.P, self.P)] * mask.shape[0]
+
+    def observe(self, sps, res, mask):
+        pass
+
+
+def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9, driver=None):
     b = binding()
     w = synth.make_weights(cfg)
     if final_gain != 1.0:
@@ -108,14 +159,10 @@ def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9):
         last.update(logits=logits, pred=pred.reshape(B, L), conf=conf.reshape(B, L))
         return last["pred"], last["conf"]
 
-    ctl = [sf.Controller(P, L, params) for _ in range(B)]
+    drv = driver(B, P, L) if driver is not None else SlowFastDriver(B, P, L, params)
     prev_pred = prev
     while stats["steps"] < max_checked_steps:
-        sps = []
-        for s in range(B):
-            sp = ctl[s].next_params(mask[s])
-            sps.append(sp if sp is not None else
-                       sf.StageParams(sf.IDLE, 0, -1, 1, params.tau_min_conf, params.tau_high_conf, params.conv_mode, P, L))
+        sps = drv.next(mask)
         if all(sp.stage == sf.IDLE for sp in sps):
             break
         # the library steps from the oracle's pre-step state
@@ -178,9 +225,7 @@ def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9):
                 stats["exact"] += 1
             else:
                 stats["loose"] += 1
-        for s in range(B):
-            if sps[s].stage != sf.IDLE:
-                ctl[s].observe(res[s][3], res[s][4], mask[s])
+        drv.observe(sps, res, mask)
         stats["steps"] += 1
     model.close()
     return stats
@@ -212,6 +257,17 @@ def test_lockstep_medium_config_first_steps():
     p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.1, tau_high_conf=0.9, conv_mode=1)
     st = lockstep(cfg, 2, p, max_checked_steps=3)
     print("lockstep medium:", st)
+
+
+def test_lockstep_low_confidence_baseline():
+    """The baseline sampler's steps (top-k of a block by confidence, k from the
+    schedule) through the same lock-step protocol: 4 blocks, 2 tokens per step."""
+    cfg = synth.CONFIGS["tiny"]
+    G = cfg["gen"]
+    st = lockstep(cfg, 2, None, final_gain=10.0,
+                  driver=lambda B, P, L: LowConfidenceDriver(B, P, L, G // 2, G // 4))
+    assert st["steps"] == G // 2
+    print("lockstep low-confidence:", st)
 
 
 def decode_params(b, p: sf.DecodeParams):
@@ -258,4 +314,51 @@ def test_decode_runs_to_completion(gain, tau_high, k_slow):
     p3 = sf.DecodeParams(max_steps=3, tau_min_conf=0.1, tau_high_conf=tau_high, conv_mode=1, k_slow=k_slow)
     steps3, _ = model.decode(g_tok, g_mask, P, decode_params(b, p3))
     assert steps3 == 3 and int(g_mask.sum()) > 0
+    model.close()
+
+
+@pytest.mark.parametrize("n_steps_div,n_blocks", [(1, 1), (2, 1), (2, 4), (4, 2)])
+def test_decode_low_confidence(n_steps_div, n_blocks):
+    """dllm_decode_low_confidence: the schedule of Section 2.1 (steps taken, tokens per
+    step), the end state, and bit-equality with the same schedule driven step by step
+    through dllm_step (same kernels, so the host loop is the only difference)."""
+    b = binding()
+    cfg = synth.CONFIGS["tiny"]
+    w = synth.make_weights(cfg)
+    w["final_norm"] = torch.full_like(w["final_norm"], 10.0)
+    wd = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in w.items()}
+    tokens, mask, _ = synth.make_state(cfg, batch=3)
+    B, L = tokens.shape
+    P, G = cfg["prompt"], cfg["gen"]
+    n_steps, block_len = G // n_steps_div, G // n_blocks
+    model = b.Model(synth.model_config(cfg), wd, B, L)
+    g_tok, g_mask = tokens.to(DEV), mask.to(DEV)
+    steps, stats = model.decode_low_confidence(g_tok, g_mask, P, n_steps, block_len if n_blocks > 1 else 0,
+                                               stats_capacity=2 * G)
+    assert steps == n_steps and int(g_mask.sum()) == 0
+    out = g_tok.cpu()
+    assert torch.equal(out[:, :P], tokens[:, :P]) and not (out == cfg["mask_id"]).any()
+    per_block = n_steps // n_blocks
+    want = [B * (sf.n_unmasked_target(block_len, per_block, j) - sf.n_unmasked_target(block_len, per_block, j - 1))
+            for _ in range(n_blocks) for j in range(1, per_block + 1)]
+    assert [s[3] for s in stats] == want and all(s[0] == B and s[1] == 0 and s[2] == 0 for s in stats)
+
+    # the same schedule, one dllm_step at a time
+    s_tok, s_mask = tokens.to(DEV), mask.to(DEV)
+    s_prev = torch.full((B, L), -1, dtype=torch.int32, device=DEV)
+    cl = b.CommitList(B, L)
+    drv = LowConfidenceDriver(B, P, L, n_steps, block_len)
+    for _ in range(n_steps):
+        sps = drv.next(s_mask.cpu().numpy())
+        model.step(s_tok, s_mask, s_prev, [b.stage_params(p.stage, p.s_cycle, p.e_cycle, p.top_k, p.tau_min_conf,
+                                                          p.tau_high_conf, p.conv_mode, p.gen_start, p.gen_end)
+                                           for p in sps], cl)
+    torch.cuda.synchronize()
+    assert torch.equal(s_tok.cpu(), out) and int(s_mask.sum()) == 0
+
+    # argument checks
+    with pytest.raises(b.DllmError):
+        model.decode_low_confidence(tokens.to(DEV), mask.to(DEV), P, n_steps, 5)       # 5 does not divide 64
+    with pytest.raises(b.DllmError):
+        model.decode_low_confidence(tokens.to(DEV), mask.to(DEV), P, 3, G // 2)        # 3 steps, 2 blocks
     model.close()
