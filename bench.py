@@ -213,6 +213,38 @@ def main():
         t_dec = time.perf_counter() - t0
         result["decode"] = {"generated_tokens_per_s": B * G / t_dec, "steps": steps, "seconds": t_dec,
                             "params": "tau_min 0.1, tau_high 0.9, K_max 8, W_hist 2, sigma2 1.0, k_slow=k_fast=1, conv_mode 1"}
+        # the baseline sampler (low-confidence remasking, one step per generated token), same kernels
+        tokens, mask = tokens0.clone(), mask0.clone()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        steps_lc, _ = model.decode_low_confidence(tokens, mask, P, G, 0)
+        t_lc = time.perf_counter() - t0
+        result["decode_low_confidence"] = {"generated_tokens_per_s": B * G / t_lc, "steps": steps_lc, "seconds": t_lc,
+                                           "params": f"N = {G} steps, one block"}
+        # random-init confidences sit near 1/V, far below the paper's thresholds; to see the fast stage
+        # commit spans, the thresholds are put at quantiles of the first step's confidences (labelled run)
+        tokens, mask, prev = tokens0.clone(), mask0.clone(), prev0.clone()
+        model.step(tokens, mask, prev, sps, out)
+        torch.cuda.synchronize()
+        conf0 = model.debug_rows(B * L)[1].view(B, L)[mask0.bool()].float()
+        tau_min_q, tau_high_q = float(conf0.quantile(0.5)), float(conf0.quantile(0.9))
+        tokens, mask = tokens0.clone(), mask0.clone()
+        dpq = b.DecodeParams(10 ** 6, 8, 2, 1, 1, 0, 1.0, tau_min_q, tau_high_q)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        steps_q, st_q = model.decode(tokens, mask, P, dpq, stats_capacity=B * G)
+        t_q = time.perf_counter() - t0
+        slow_ms = [s[4] for s in st_q if s[0] > 0 and s[1] == 0]
+        fast_ms = [s[4] for s in st_q if s[1] > 0 and s[0] == 0]
+        fast_commits = [s[3] for s in st_q if s[1] > 0 and s[0] == 0]
+        result["decode_quantile_thresholds"] = {
+            "generated_tokens_per_s": B * G / t_q, "steps": steps_q, "seconds": t_q,
+            "steps_vs_low_confidence": steps_q / max(steps_lc, 1),
+            "slow_steps": len(slow_ms), "fast_steps": len(fast_ms),
+            "slow_step_ms": sum(slow_ms) / max(len(slow_ms), 1), "fast_step_ms": sum(fast_ms) / max(len(fast_ms), 1),
+            "tokens_per_fast_step": sum(fast_commits) / max(len(fast_commits), 1),
+            "params": f"tau_min = median ({tau_min_q:.3e}), tau_high = 90th percentile ({tau_high_q:.3e}) of the first "
+                      "step's confidences, K_max 8, W_hist 2, sigma2 1.0, k_slow=k_fast=1, conv_mode 0"}
         result["cpu_baseline"] = cpu_baseline_step(mc, weights, tokens0)
         model.close()
         del model, weights
