@@ -136,6 +136,59 @@ def swiglu(gate, up):
     return out
 
 
+def _pack(cfg: dict, weights: dict):
+    c = _Config(*[int(cfg[k]) for k in
+                  ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab", "mask_id")],
+                float(cfg["rms_eps"]), float(cfg["rope_theta"]))
+    nl = c.n_layers
+    keep = []
+
+    def arr(name):
+        lst = [_u16(a) for a in weights[name]]
+        assert len(lst) == nl
+        keep.append(lst)
+        return (C.c_void_p * max(nl, 1))(*[a.ctypes.data for a in lst])
+
+    single = {k: _u16(weights[k]) for k in ("embed", "lm_head", "final_norm")}
+    arrays = {k: arr(k) for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")}
+    w = _Weights(single["embed"].ctypes.data, single["lm_head"].ctypes.data,
+                 single["final_norm"].ctypes.data,
+                 *[C.cast(arrays[k], C.POINTER(C.c_void_p)) for k in
+                   ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")])
+    return c, w, (keep, single, arrays)
+
+
+class KVCache:
+    """Per-layer keys (after RoPE) and values of every position, float64: the
+    features kept by out-of-span caching."""
+
+    def __init__(self, cfg: dict, B: int, L: int):
+        self.k = np.zeros((int(cfg["n_layers"]), B * L, int(cfg["d_model"])), dtype=np.float64)
+        self.v = np.zeros_like(self.k)
+
+
+def forward_cached(cfg: dict, weights: dict, tokens, cache: KVCache, rows, skip=None):
+    """Forward that recomputes the positions with skip == 0 (all of them when
+    skip is None), lets them attend to the cached keys/values of the skipped
+    ones, refreshes the cache rows of the recomputed ones, and returns the
+    logits [len(rows), V] of the listed rows (indices into B*L, none skipped)."""
+    c, w, keep = _pack(cfg, weights)
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    B, L = tokens.shape
+    assert cache.k.shape == (c.n_layers, B * L, c.d_model) and cache.k.flags.c_contiguous
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    if skip is not None:
+        skip = np.ascontiguousarray(skip, dtype=np.uint8).reshape(-1)
+        assert skip.shape[0] == B * L
+    logits = np.empty((rows.shape[0], c.vocab), dtype=np.float64)
+    rc = lib().orc_forward_cached(C.byref(c), C.byref(w), _p(tokens), C.c_int(B), C.c_int(L),
+                                  _p(skip) if skip is not None else None, _p(cache.k), _p(cache.v),
+                                  _p(rows), C.c_int(rows.shape[0]), _p(logits))
+    if rc != 0:
+        raise ValueError(f"orc_forward_cached failed with {rc}")
+    return logits
+
+
 def forward(cfg: dict, weights: dict, tokens, rows=None):
     """cfg: dict with the orc_config fields; weights: dict of uint16 arrays
     (per-layer entries are lists).  tokens [B, L] -> logits float64 [B*L, V],

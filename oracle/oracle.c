@@ -261,6 +261,147 @@ int orc_forward(const orc_config *c, const orc_weights *w, const int32_t *tokens
     return 0;
 }
 
+/* Attention of Lq queries over Lk keys (one sequence, no mask): q, out are
+ * [Lq][n_heads][dh]; k, v are [Lk][n_heads][dh]. */
+static void orc_attention_qk(const double *q, int Lq, const double *k, const double *v, int Lk, int n_heads, int dh,
+                             double *out)
+{
+    double scale = 1.0 / sqrt((double)dh);
+#pragma omp parallel for collapse(2)
+    for (int i = 0; i < Lq; ++i) {
+        for (int h = 0; h < n_heads; ++h) {
+            double *p = (double *)malloc(sizeof(double) * Lk);
+            const double *qi = q + ((int64_t)i * n_heads + h) * dh;
+            double m = -INFINITY;
+            for (int j = 0; j < Lk; ++j) {
+                const double *kj = k + ((int64_t)j * n_heads + h) * dh;
+                double s = 0.0;
+                for (int t = 0; t < dh; ++t) s += qi[t] * kj[t];
+                p[j] = s * scale;
+                if (p[j] > m) m = p[j];
+            }
+            double z = 0.0;
+            for (int j = 0; j < Lk; ++j) {
+                p[j] = exp(p[j] - m);
+                z += p[j];
+            }
+            double *o = out + ((int64_t)i * n_heads + h) * dh;
+            for (int t = 0; t < dh; ++t) o[t] = 0.0;
+            for (int j = 0; j < Lk; ++j) {
+                const double *vj = v + ((int64_t)j * n_heads + h) * dh;
+                double w = p[j] / z;
+                for (int t = 0; t < dh; ++t) o[t] += w * vj[t];
+            }
+            free(p);
+        }
+    }
+}
+
+/* Forward with out-of-span caching (Section 3.3, "Out-of-Span Caching"; the
+ * "cache features for position i" branch of Algorithm 1's fast phase).  The
+ * features kept per position are, for every layer, its key (after the rotary
+ * embedding) and its value: all that other positions ever read from it.
+ *   kcache, vcache  [n_layers][B*L][d_model], in/out
+ *   skip            [B*L] or NULL; skip[r] != 0: position r is not recomputed,
+ *                   its cached keys/values of every layer are used as they are
+ * Every other position is recomputed from the current tokens, attends to all
+ * L positions of its sequence (fresh keys/values of recomputed positions,
+ * cached ones of skipped positions), and overwrites its own cache rows.  With
+ * skip == NULL this is the full forward that also fills the cache.
+ *   rows / n_rows   rows (indices into B*L, none of them skipped) that get a
+ *                   vocabulary projection; logits is [n_rows][vocab]. */
+int orc_forward_cached(const orc_config *c, const orc_weights *w, const int32_t *tokens, int B, int L,
+                       const uint8_t *skip, double *kcache, double *vcache, const int32_t *rows, int n_rows,
+                       double *logits)
+{
+    const int d = c->d_model, H = c->n_heads, dh = c->head_dim, f = c->d_ffn;
+    if (H * dh != d || !kcache || !vcache || !rows) return -1;
+    const int64_t M = (int64_t)B * L;
+    /* the positions that are recomputed, in order; cidx maps a row to its index among them */
+    int32_t *act = malloc(sizeof(int32_t) * M), *cidx = malloc(sizeof(int32_t) * M);
+    int32_t *first = malloc(sizeof(int32_t) * (B + 1));
+    if (!act || !cidx || !first) return -2;
+    int64_t Ma = 0;
+    for (int b = 0; b < B; ++b) {
+        first[b] = (int32_t)Ma;
+        for (int i = 0; i < L; ++i) {
+            int64_t r = (int64_t)b * L + i;
+            cidx[r] = -1;
+            if (!skip || !skip[r]) { cidx[r] = (int32_t)Ma; act[Ma++] = (int32_t)r; }
+        }
+    }
+    first[B] = (int32_t)Ma;
+    if (Ma == 0) { free(act); free(cidx); free(first); return n_rows == 0 ? 0 : -4; }
+    double *x = malloc(sizeof(double) * Ma * d);
+    double *h = malloc(sizeof(double) * Ma * d);
+    double *qkv = malloc(sizeof(double) * Ma * 3 * d);
+    double *q = malloc(sizeof(double) * Ma * d);
+    double *k = malloc(sizeof(double) * Ma * d);
+    double *v = malloc(sizeof(double) * Ma * d);
+    double *att = malloc(sizeof(double) * Ma * d);
+    double *proj = malloc(sizeof(double) * Ma * d);
+    double *gu = malloc(sizeof(double) * Ma * 2 * f);
+    double *gate = malloc(sizeof(double) * Ma * f);
+    double *up = malloc(sizeof(double) * Ma * f);
+    double *actv = malloc(sizeof(double) * Ma * f);
+    int32_t *pos = malloc(sizeof(int32_t) * Ma);
+    if (!x || !h || !qkv || !q || !k || !v || !att || !proj || !gu || !gate || !up || !actv || !pos) return -2;
+
+    for (int64_t a = 0; a < Ma; ++a) {
+        int32_t t = tokens[act[a]];
+        if (t < 0 || t >= c->vocab) return -3;
+        for (int j = 0; j < d; ++j) x[a * d + j] = orc_bf16_to_f64(w->embed[(int64_t)t * d + j]);
+        pos[a] = act[a] % L;
+    }
+    for (int l = 0; l < c->n_layers; ++l) {
+        double *kc = kcache + (int64_t)l * M * d, *vc = vcache + (int64_t)l * M * d;
+        orc_rmsnorm(x, w->attn_norm[l], Ma, d, c->rms_eps, h);
+        orc_linear(h, w->wqkv[l], Ma, d, 3 * d, qkv);
+        for (int64_t a = 0; a < Ma; ++a)
+            for (int j = 0; j < d; ++j) {
+                q[a * d + j] = qkv[a * 3 * d + j];
+                k[a * d + j] = qkv[a * 3 * d + d + j];
+                v[a * d + j] = qkv[a * 3 * d + 2 * d + j];
+            }
+        orc_rope(q, pos, Ma, H, dh, c->rope_theta);
+        orc_rope(k, pos, Ma, H, dh, c->rope_theta);
+        /* recomputed positions refresh their cache rows; skipped ones keep theirs */
+        for (int64_t a = 0; a < Ma; ++a) {
+            memcpy(kc + (int64_t)act[a] * d, k + a * d, sizeof(double) * d);
+            memcpy(vc + (int64_t)act[a] * d, v + a * d, sizeof(double) * d);
+        }
+        for (int b = 0; b < B; ++b) {
+            int Lq = first[b + 1] - first[b];
+            if (Lq == 0) continue;
+            int64_t qo = (int64_t)first[b] * d, ko = (int64_t)b * L * d;
+            orc_attention_qk(q + qo, Lq, kc + ko, vc + ko, L, H, dh, att + qo);
+        }
+        orc_linear(att, w->wo[l], Ma, d, d, proj);
+        for (int64_t i = 0; i < Ma * d; ++i) x[i] += proj[i];
+        orc_rmsnorm(x, w->ffn_norm[l], Ma, d, c->rms_eps, h);
+        orc_linear(h, w->w_gate_up[l], Ma, d, 2 * f, gu);
+        for (int64_t a = 0; a < Ma; ++a)
+            for (int j = 0; j < f; ++j) {
+                gate[a * f + j] = gu[a * 2 * f + j];
+                up[a * f + j] = gu[a * 2 * f + f + j];
+            }
+        orc_swiglu(gate, up, Ma * f, actv);
+        orc_linear(actv, w->w_down[l], Ma, f, d, proj);
+        for (int64_t i = 0; i < Ma * d; ++i) x[i] += proj[i];
+    }
+    orc_rmsnorm(x, w->final_norm, Ma, d, c->rms_eps, h);
+    for (int i = 0; i < n_rows; ++i) {
+        if (rows[i] < 0 || rows[i] >= M || cidx[rows[i]] < 0) return -4;
+        memcpy(x + (int64_t)i * d, h + (int64_t)cidx[rows[i]] * d, sizeof(double) * d);
+    }
+    if (n_rows > Ma) return -4;
+    orc_linear(x, w->lm_head, n_rows, d, c->vocab, logits);
+
+    free(x); free(h); free(qkv); free(q); free(k); free(v); free(att); free(proj);
+    free(gu); free(gate); free(up); free(actv); free(pos); free(act); free(cidx); free(first);
+    return 0;
+}
+
 /* ---- per-position greedy decode and confidence (eq. 3, confidence eq.) --- */
 
 /* Softmax of one logits row by definition, with the [MASK] id removed from

@@ -27,6 +27,14 @@ Readings taken where the paper is silent or at odds with itself:
 * The fast stage repeats until no mask is left in [s_cycle, e_cycle]; then
   s_cycle <- e_cycle + 1.
 * Every decision on a confidence is taken on its binary32 value.
+* Out-of-span caching (optional, DecodeParams.out_of_span_cache): the first
+  step of a fast stage is a complete prediction whose confidences cover
+  [s_cycle, gen_end); the masked positions i > e_cycle with confidence below
+  tau_min form the stage's cached set.  Their "features" are their keys and
+  values in every layer as computed in that step.  The later steps of the
+  stage do not recompute them: all other positions are recomputed from the
+  current tokens and attend to those cached keys/values.  The set is dropped
+  when the stage ends.  Prompt and committed positions are always recomputed.
 """
 from __future__ import annotations
 
@@ -36,6 +44,7 @@ from typing import Callable, List, Optional, Sequence, Tuple
 import numpy as np
 
 SLOW, FAST, IDLE = 0, 1, 2
+CACHE_OFF, CACHE_REFRESH, CACHE_REUSE = 0, 1, 2
 
 
 @dataclass
@@ -50,6 +59,15 @@ class StageParams:
     conv_mode: int
     gen_start: int
     gen_end: int
+    cache_mode: int = 0   # CACHE_OFF, CACHE_REFRESH (first fast step of a stage) or CACHE_REUSE
+
+    def eval_window(self) -> Tuple[int, int]:
+        """Inclusive span whose masked positions get a prediction and a confidence:
+        the decision window, widened to the end of the sequence in a refresh step
+        (the confidences right of the span decide what is cached)."""
+        if self.stage == FAST and self.cache_mode == CACHE_REFRESH:
+            return self.s_cycle, self.gen_end - 1
+        return self.window()
 
     def window(self) -> Tuple[int, int]:
         """Inclusive span the step looks at: [s_cycle, end of sequence] in the
@@ -72,11 +90,12 @@ class DecodeParams:
     k_slow: int = 1
     k_fast: int = 1
     conv_mode: int = 0
+    out_of_span_cache: bool = False
 
 
 def active_rows(sp: StageParams, mask: np.ndarray) -> np.ndarray:
     """Positions whose prediction the step needs: masked and inside the window."""
-    lo, hi = sp.window()
+    lo, hi = sp.eval_window()
     act = np.zeros(mask.shape[0], dtype=np.uint8)
     for i in range(max(lo, 0), min(hi, mask.shape[0] - 1) + 1):
         if mask[i]:
@@ -121,13 +140,26 @@ Predictor = Callable[[np.ndarray, np.ndarray], Tuple[np.ndarray, np.ndarray]]
 the greedy estimate and its confidence at the active positions."""
 
 
-def step(predict: Predictor, tokens, mask, prev_pred, sps: Sequence[StageParams]):
+def step(predict: Predictor, tokens, mask, prev_pred, sps: Sequence[StageParams], skip=None):
     """One denoising step on a batch, in place.  Returns, per sequence,
     (commit positions, committed tokens, their confidences, e_cand,
-    first_masked, masks left in the sequence)."""
+    first_masked, masks left in the sequence, the step's confidences).
+
+    With out-of-span caching some sequences carry cache_mode != CACHE_OFF; the
+    predictor must then offer predict.cached(tokens, active, skip) where
+    skip[b, i] != 0 marks the positions of CACHE_REUSE sequences that are not
+    recomputed (it refreshes the cached features of every other position)."""
     B, L = tokens.shape
     active = np.stack([active_rows(sps[b], mask[b]) for b in range(B)])
-    pred, conf = predict(tokens, active)
+    if any(sp.cache_mode != CACHE_OFF for sp in sps):
+        sk = np.zeros((B, L), dtype=np.uint8)
+        for b in range(B):
+            if sps[b].cache_mode == CACHE_REUSE:
+                sk[b] = skip[b]
+                assert not np.any(sk[b] & active[b]), "a skipped position has no prediction"
+        pred, conf = predict.cached(tokens, active, sk)
+    else:
+        pred, conf = predict(tokens, active)
     out = []
     for b in range(B):
         commit, e_cand, first_masked = select(sps[b], mask[b], pred[b], conf[b], prev_pred[b])
@@ -139,7 +171,7 @@ def step(predict: Predictor, tokens, mask, prev_pred, sps: Sequence[StageParams]
         for i in range(L):                     # remember this step's estimate
             if active[b, i]:
                 prev_pred[b, i] = pred[b, i]
-        out.append((commit, toks, cfs, e_cand, first_masked, int(mask[b].sum())))
+        out.append((commit, toks, cfs, e_cand, first_masked, int(mask[b].sum()), np.asarray(conf[b], dtype=np.float32)))
     return out
 
 
@@ -157,6 +189,8 @@ class Controller:
     step_count: int = field(init=False, default=0)   # steps of this slow stage
     steps: int = field(init=False, default=0)        # N - k
     log: List[Tuple[int, int, int]] = field(init=False, default_factory=list)
+    fast_steps: int = field(init=False, default=0)   # steps of this fast stage
+    skip: Optional[np.ndarray] = field(init=False, default=None)   # cached set of this fast stage
 
     def __post_init__(self):
         self.s_cycle = self.gen_start
@@ -166,24 +200,29 @@ class Controller:
         if not np.any(mask) or self.steps >= self.p.max_steps:
             return None
         slow = self.stage == SLOW
+        cache = CACHE_OFF
+        if not slow and self.p.out_of_span_cache:
+            cache = CACHE_REFRESH if self.fast_steps == 0 else CACHE_REUSE
         return StageParams(self.stage, self.s_cycle, self.e_cycle if not slow else self.gen_end - 1,
                            self.p.k_slow if slow else self.p.k_fast,
                            self.p.tau_min_conf, self.p.tau_high_conf, self.p.conv_mode,
-                           self.gen_start, self.gen_end)
+                           self.gen_start, self.gen_end, cache)
 
     def _start_slow(self):
         self.stage, self.history, self.step_count = SLOW, [], 0
+        self.fast_steps, self.skip = 0, None
 
     def _enter_fast(self, e, mask):
         e = min(max(e, self.s_cycle), self.gen_end - 1)
         self.e_cycle = e
         if np.any(mask[self.s_cycle:e + 1]):
-            self.stage = FAST
+            self.stage, self.fast_steps, self.skip = FAST, 0, None
         else:                                   # span already clean: next cycle
             self.s_cycle = e + 1
             self._start_slow()
 
-    def observe(self, e_cand: int, first_masked: int, mask_after) -> None:
+    def observe(self, e_cand: int, first_masked: int, mask_after, conf=None) -> None:
+        """conf: the step's confidences (needed after a refresh step only)."""
         self.steps += 1
         self.log.append((self.stage, self.s_cycle, self.e_cycle))
         if self.stage == SLOW:
@@ -196,6 +235,15 @@ class Controller:
             elif self.step_count >= self.p.k_max:
                 self._enter_fast(e_k, mask_after)
         else:
+            if self.p.out_of_span_cache and self.fast_steps == 0:
+                # Out-of-span caching: masked positions right of the span whose confidence in
+                # this (complete) step is below tau_min are not recomputed for the rest of the stage
+                L = len(mask_after)
+                self.skip = np.zeros(L, dtype=np.uint8)
+                for i in range(self.e_cycle + 1, self.gen_end):
+                    if mask_after[i] and np.float32(conf[i]) < np.float32(self.p.tau_min_conf):
+                        self.skip[i] = 1
+            self.fast_steps += 1
             if not np.any(mask_after[self.s_cycle:self.e_cycle + 1]):
                 self.s_cycle = self.e_cycle + 1
                 self._start_slow()
@@ -222,11 +270,12 @@ def decode(predict: Predictor, tokens, mask, gen_start: int, gen_end: int, p: De
             sps.append(sp)
         if not live:
             return steps
-        res = step(predict, tokens, mask, prev_pred, sps)
+        skip = [ctl[b].skip for b in range(B)]
+        res = step(predict, tokens, mask, prev_pred, sps, skip)
         steps += 1
         for b in range(B):
             if sps[b].stage != IDLE:
-                ctl[b].observe(res[b][3], res[b][4], mask[b])
+                ctl[b].observe(res[b][3], res[b][4], mask[b], res[b][6])
         if trace is not None:
             trace.append((sps, res))
 

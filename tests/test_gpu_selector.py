@@ -94,7 +94,7 @@ def run_case(B, L, V, mask_id, logits, mask, prev, sps, capacity=None):
     got = out.to_host()
     n_amb = 0
     for s in range(B):
-        commit, toks, cfs, e_cand, first, left = res[s]
+        commit, toks, cfs, e_cand, first, left = res[s][:6]
         g_pos, g_toks, g_cfs, g_e, g_first, g_left = got[s]
         assert g_first == first
         if ambiguous(sps[s], mask_before[s], o_conf[s]):

@@ -192,7 +192,7 @@ def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9, driv
 
         g_tok, g_mask, g_prev = g_tok.cpu().numpy(), g_mask.cpu().numpy(), g_prev.cpu().numpy()
         for s in range(B):
-            commit, toks, cfs, e_cand, first, left = res[s]
+            commit, toks, cfs, e_cand, first, left = res[s][:6]
             g_pos, g_toks, g_cfs, g_e, g_first, g_left = got[s]
             rb = Robust(sps[s], mask_before[s], last["conf"][s], last["pred"][s], prev_before[s], gap[s], delta,
                         2 * eps_abs + 2.0 ** -7 * top)

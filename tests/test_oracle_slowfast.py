@@ -210,7 +210,7 @@ def test_decode_invariants_on_a_small_model(conv_mode, quantile):
     committed = [dict() for _ in range(2)]
     for sps, res in trace:
         for b in range(2):
-            commit, toks, cfs, e_cand, first, left = res[b]
+            commit, toks, cfs, e_cand, first, left = res[b][:6]
             if sps[b].stage == sf.IDLE:
                 assert commit == []
                 continue
@@ -315,3 +315,112 @@ def test_low_confidence_decode_skips_steps_whose_target_is_met():
         return pred.copy(), np.where(active == 1, conf, 0).astype(np.float32)
     steps = sf.decode_low_confidence(predict, tokens, mask, P, G, 8, None)
     assert steps == 4 == len(calls) and not mask.any()
+
+
+# ---- out-of-span caching (Section 3.3) ----------------------------------------------
+
+class RecordingPredictor:
+    """State-independent confidences; records how it was called."""
+
+    def __init__(self, conf, pred):
+        self.conf, self.pred, self.calls = conf, pred, []
+
+    def __call__(self, tokens, active):
+        self.calls.append(("plain", active.copy(), None))
+        return self.pred.copy(), np.where(active == 1, self.conf, 0).astype(np.float32)
+
+    def cached(self, tokens, active, skip):
+        self.calls.append(("cached", active.copy(), skip.copy()))
+        return self.pred.copy(), np.where(active == 1, self.conf, 0).astype(np.float32)
+
+
+def test_out_of_span_caching_protocol():
+    # positions 2..7 confident, 8..13 not: slow, slow -> e_cycle = 7; the fast stage needs two steps
+    # (top-1 fallback is avoided: 0.95 > tau_high, but convergence holds from the second look only)
+    P, L = 2, 14
+    conf = np.full((1, L), 0.05, np.float32); conf[0, 2:8] = 0.95; conf[0, 12] = 0.5
+    pred = np.arange(L, dtype=np.int32)[None] + 200
+    tokens = np.full((1, L), 999, np.int32); mask = np.zeros((1, L), np.uint8); mask[:, P:] = 1
+    rp = RecordingPredictor(conf, pred)
+    trace = []
+    p = sf.DecodeParams(max_steps=100, tau_min_conf=0.1, tau_high_conf=0.9, conv_mode=0, k_fast=1,
+                        out_of_span_cache=True)
+    # make the fast stage last: only one position clears tau_high per step
+    conf[0, 2:8] = [0.95, 0.5, 0.5, 0.5, 0.5, 0.5]
+    steps = sf.decode(rp, tokens, mask, P, L, p, trace)
+    assert not mask.any()
+    modes = [(sps[0].stage, sps[0].cache_mode) for sps, _ in trace]
+    # every fast stage starts with a refresh and continues with reuse steps; slow steps never cache
+    for i, (stage, mode) in enumerate(modes):
+        if stage == sf.SLOW:
+            assert mode == sf.CACHE_OFF
+        else:
+            first = i == 0 or modes[i - 1][0] == sf.SLOW or trace[i][0][0].s_cycle != trace[i - 1][0][0].s_cycle
+            assert mode == (sf.CACHE_REFRESH if first else sf.CACHE_REUSE)
+    assert any(m == sf.CACHE_REUSE for _, m in modes)
+    kinds = [c[0] for c in rp.calls]
+    assert kinds == ["plain" if m == sf.CACHE_OFF else "cached" for _, m in modes]
+    cur_mask = np.zeros(L, np.uint8); cur_mask[P:] = 1
+    for (kind, active, skip), (sps, res) in zip(rp.calls, trace):
+        sp = sps[0]
+        mask_before = cur_mask.copy()
+        cur_mask[res[0][0]] = 0
+        if sp.cache_mode == sf.CACHE_REFRESH:
+            # confidences right of the span are evaluated, nothing is skipped
+            assert not skip.any()
+            lo, hi = sp.eval_window()
+            assert (lo, hi) == (sp.s_cycle, L - 1) and active[0, sp.e_cycle + 1:].sum() > 0
+        if sp.cache_mode == sf.CACHE_REUSE:
+            # skipped = masked, right of the span, confidence below tau_min at the refresh step
+            want = np.zeros(L, np.uint8)
+            for i in range(sp.e_cycle + 1, L):
+                want[i] = 1 if conf[0, i] < 0.1 else 0
+            assert np.array_equal(skip[0], want & mask_before) and skip[0].sum() > 0
+            assert not (skip[0][:sp.e_cycle + 1]).any() and not (skip & active).any()
+            assert skip[0, 12] == 0                          # 0.5 >= tau_min: recomputed
+            assert all(sp.s_cycle <= i <= sp.e_cycle for i in res[0][0])
+
+
+def test_caching_does_not_change_a_state_independent_trajectory():
+    # when predictions do not depend on the state, stale features cannot matter:
+    # the decode with caching must take exactly the steps of the decode without
+    rng = np.random.default_rng(12)
+    P, G = 3, 40
+    L = P + G
+    conf = (rng.random((2, L)) ** 3).astype(np.float32)
+    pred = rng.integers(0, 50, (2, L)).astype(np.int32)
+    outs = []
+    for cache in (False, True):
+        tokens = np.full((2, L), 99, np.int32); mask = np.zeros((2, L), np.uint8); mask[:, P:] = 1
+        trace = []
+        p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.2, tau_high_conf=0.6, out_of_span_cache=cache)
+        steps = sf.decode(RecordingPredictor(conf, pred), tokens, mask, P, L, p, trace)
+        outs.append((steps, [[r[0] for r in res] for _, res in trace], tokens.copy()))
+    assert outs[0][0] == outs[1][0] and outs[0][1] == outs[1][1] and np.array_equal(outs[0][2], outs[1][2])
+
+
+def test_cached_decode_on_a_small_model_keeps_the_invariants():
+    from util import OraclePredictor
+    cfg = dict(synth.CONFIGS["tiny"], vocab=257, mask_id=256, prompt=6, gen=24, d_model=64, n_heads=2,
+               head_dim=32, d_ffn=96, n_layers=2)
+    w = synth.make_weights(cfg, std=0.25)
+    tokens, mask, _ = synth.make_state(cfg, batch=2)
+    tokens, mask = tokens.numpy().copy(), mask.numpy().copy()
+    B, L = tokens.shape
+    P = cfg["prompt"]
+    predict = OraclePredictor(synth.model_config(cfg), weights_bits(w), B, L)
+    _, c0 = predict(tokens, mask)
+    tau_high = float(np.quantile(c0[mask == 1], 0.8)); tau_min = float(np.quantile(c0[mask == 1], 0.5))
+    predict.recomputed.clear()
+    p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=tau_min, tau_high_conf=tau_high, out_of_span_cache=True)
+    trace = []
+    steps = sf.decode(predict, tokens, mask, P, L, p, trace)
+    assert not mask.any() and steps <= B * cfg["gen"] and not (tokens == cfg["mask_id"]).any()
+    reuse = [n for (sps, _), n in zip(trace, predict.recomputed) if any(sp.cache_mode == sf.CACHE_REUSE for sp in sps)]
+    assert reuse and min(reuse) < B * L                   # some steps really skipped positions
+    for sps, res in trace:
+        for b in range(B):
+            if sps[b].stage != sf.IDLE:
+                assert len(res[b][0]) >= 1
+                lo, hi = sps[b].window()
+                assert all(lo <= i <= hi for i in res[b][0])
