@@ -128,6 +128,10 @@ typedef struct {
     int32_t k_slow, k_fast;
     int32_t conv_mode;
     float sigma2_stable, tau_min_conf, tau_high_conf;
+    int32_t out_of_span_cache; /* 0 / 1: Section 3.3's Out-of-Span Caching in the fast stage: the first step of
+                                  a fast stage is a complete prediction; masked positions right of e_cycle whose
+                                  confidence there is below tau_min_conf are not recomputed (their keys/values
+                                  are reused) in the later steps of that stage */
 } dllm_decode_params;
 
 /* One record per denoising step of dllm_decode. */
@@ -161,6 +165,33 @@ const char *dllm_last_error(const dllm_handle *h);
  * its window is not an error: n_commit = 0. */
 int dllm_step(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *mask, int32_t *prev_pred,
               const dllm_stage_params *sp, const dllm_commit_list *out);
+
+/* dllm_step with out-of-span caching (Section 3.3, "Out-of-Span Caching"; Algorithm 1, fast
+ * phase: "cache features for position i").  The features kept per position are its keys (after
+ * the rotary embedding) and values in every layer.  Per sequence, cache_mode is
+ *   DLLM_CACHE_OFF      nothing special for this sequence
+ *   DLLM_CACHE_REFRESH  first step of a fast stage: a complete prediction whose confidences
+ *                       cover [s_cycle, gen_end), so that the caller can pick the positions to
+ *                       cache (the paper: masked, right of e_cycle, confidence < tau_min_conf;
+ *                       read them with dllm_debug_rows); selection stays inside [s_cycle, e_cycle]
+ *   DLLM_CACHE_REUSE    later steps of the stage: positions with skip[b][i] != 0 are not
+ *                       recomputed; all others are, attend to the cached keys/values of the
+ *                       skipped ones, and refresh their own cache rows
+ * REFRESH and REUSE require the fast stage.  In any step with a sequence in REFRESH or REUSE the
+ * keys/values of every recomputed position of the batch are written to the cache (allocated on
+ * first use: n_layers x max_batch x max_seq x 3 d_model bf16).
+ *   cache_mode  host int32 [B]
+ *   skip        host uint8 [B][L], may be NULL when no sequence is in REUSE; read before the
+ *               call returns; skip[b][i] != 0 requires i > e_cycle of sequence b
+ * Errors beyond dllm_step's: DLLM_ESTATE when positions are skipped before any step filled the
+ * cache; DLLM_EINVAL for a skipped position at or left of e_cycle, or a model whose d_model is
+ * not a multiple of 64 (the cached path uses the fused QKV + RoPE kernel only). */
+#define DLLM_CACHE_OFF 0
+#define DLLM_CACHE_REFRESH 1
+#define DLLM_CACHE_REUSE 2
+int dllm_step_cached(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *mask, int32_t *prev_pred,
+                     const dllm_stage_params *sp, const int32_t *cache_mode, const uint8_t *skip,
+                     const dllm_commit_list *out);
 
 /* Full SlowFast decode (Algorithm 1) of B sequences that share gen_start and
  * gen_end = L: alternates exploratory (slow) and accelerated (fast) stages per

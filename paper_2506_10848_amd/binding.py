@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libdllm.so")
 
 OK, EINVAL, ENOMEM, EHIP, ECAPACITY, ESTATE = 0, -1, -2, -3, -4, -5
 STAGE_SLOW, STAGE_FAST, STAGE_IDLE = 0, 1, 2
+CACHE_OFF, CACHE_REFRESH, CACHE_REUSE = 0, 1, 2
 MAX_BATCH = 64
 
 
@@ -52,7 +53,7 @@ class CommitListC(C.Structure):
 class DecodeParams(C.Structure):
     _fields_ = [("max_steps", C.c_int32), ("k_max", C.c_int32), ("w_hist", C.c_int32), ("k_slow", C.c_int32),
                 ("k_fast", C.c_int32), ("conv_mode", C.c_int32), ("sigma2_stable", C.c_float),
-                ("tau_min_conf", C.c_float), ("tau_high_conf", C.c_float)]
+                ("tau_min_conf", C.c_float), ("tau_high_conf", C.c_float), ("out_of_span_cache", C.c_int32)]
 
 
 class StepStat(C.Structure):
@@ -60,7 +61,7 @@ class StepStat(C.Structure):
                 ("ms", C.c_float)]
 
 
-EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_decode", "dllm_decode_low_confidence", "dllm_debug_logits",
+EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_step_cached", "dllm_decode", "dllm_decode_low_confidence", "dllm_debug_logits",
            "dllm_debug_rows", "dllm_profile_begin", "dllm_profile_end", "dllm_forward", "dllm_select", "dllm_op_linear", "dllm_op_linear_swiglu",
            "dllm_op_add_rmsnorm", "dllm_op_rope", "dllm_op_linear_qkv_rope", "dllm_op_attention"]
 
@@ -204,6 +205,20 @@ class Model:
         cl = out.c_struct()
         _check(lib().dllm_step(self._h, B, L, _ptr(tokens), _ptr(mask), _ptr(prev_pred), _sp_array(sps),
                                C.byref(cl)), self._h)
+
+    def step_cached(self, tokens, mask, prev_pred, sps, cache_mode, skip, out: "CommitList") -> None:
+        """dllm_step_cached: cache_mode is a sequence of B ints, skip a host uint8 array [B, L] or None."""
+        _dev(tokens, torch.int32, "tokens"); _dev(mask, torch.uint8, "mask"); _dev(prev_pred, torch.int32, "prev_pred")
+        B, L = tokens.shape
+        cl = out.c_struct()
+        modes = (C.c_int32 * B)(*[int(m) for m in cache_mode])
+        sk = None
+        if skip is not None:
+            import numpy as np
+            sk = np.ascontiguousarray(skip, dtype=np.uint8)
+            assert sk.shape == (B, L)
+        _check(lib().dllm_step_cached(self._h, B, L, _ptr(tokens), _ptr(mask), _ptr(prev_pred), _sp_array(sps), modes,
+                                      C.c_void_p(sk.ctypes.data) if sk is not None else None, C.byref(cl)), self._h)
 
     def decode(self, tokens, mask, gen_start: int, params: DecodeParams, stats_capacity: int = 0):
         _dev(tokens, torch.int32, "tokens"); _dev(mask, torch.uint8, "mask")

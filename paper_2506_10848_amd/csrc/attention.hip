@@ -53,8 +53,10 @@ __device__ __forceinline__ int k_swz(int row)
 }
 
 template <int DH, int KVSPLIT>
-__global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__restrict__ qkv,
-                                                             uint16_t *__restrict__ out, int L, int H)
+__global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__restrict__ qsrc,
+                                                             const uint16_t *__restrict__ kvsrc,
+                                                             uint16_t *__restrict__ out, int L, int H, int nq,
+                                                             SeqRows rows)
 {
     constexpr int KSTEPS = DH / 16;  // MFMA K steps over the head dimension
     constexpr int DSUB = DH / 32;    // 32-row sub-tiles of O^T
@@ -71,7 +73,7 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__r
     const size_t ld = (size_t)3 * d;
     // Workgroups of one (batch, head) share its K and V: give them ids congruent mod 8, which
     // the dispatcher places on the same XCD, so each K/V tile crosses into one L2 only.
-    const int nq = (L + QT - 1) / QT, nbh = (int)gridDim.x / nq;
+    const int nbh = (int)gridDim.x / nq;
     int qblk, bh;
     {
         const int pid = blockIdx.x, n8 = nbh & ~7, head = nq * n8;
@@ -86,11 +88,14 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__r
         }
     }
     const int h = bh % H, b = bh / H;
+    // queries: rows [qfirst, qfirst + Lq) of qsrc; keys and values: the L rows of sequence b in kvsrc
+    const int qfirst = rows.first[b], Lq = rows.count[b];
+    if (qblk * QT >= Lq) return;  // uniform over the workgroup
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int half = KVSPLIT == 2 ? wave >> 1 : 0, qgroup = KVSPLIT == 2 ? wave & 1 : wave, htid = tid & (HT - 1);
     const int l32 = lane & 31, g = lane >> 5;
     const int q0 = qblk * QT + qgroup * 32;
-    const uint16_t *base = qkv + (size_t)b * L * ld;
+    const uint16_t *base = kvsrc + (size_t)b * L * ld;
     const float c = kLog2e / sqrtf((float)DH);
 
     // key steps of this half
@@ -103,8 +108,8 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__r
     // Q fragments (B operand): lane (query l32, half g) holds dims t*16 + g*8 .. +8
     bf16x8 qf[KSTEPS];
     {
-        const int qrow = min(q0 + l32, L - 1);
-        const uint16_t *qp = base + (size_t)qrow * ld + (size_t)h * DH + g * 8;
+        const int qrow = qfirst + min(q0 + l32, Lq - 1);
+        const uint16_t *qp = qsrc + (size_t)qrow * ld + (size_t)h * DH + g * 8;
 #pragma unroll
         for (int t = 0; t < KSTEPS; ++t) qf[t] = as_bf16x8(*reinterpret_cast<const uint4 *>(qp + t * 16));
     }
@@ -281,8 +286,8 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__r
     }
     const float inv = 1.0f / (l_tot * a0 + l1 * a1);
     const int q = q0 + l32;
-    if (q < L) {
-        uint16_t *op = out + ((size_t)b * L + q) * d + (size_t)h * DH;
+    if (q < Lq) {
+        uint16_t *op = out + ((size_t)qfirst + q) * d + (size_t)h * DH;
 #pragma unroll
         for (int i = 0; i < DSUB; ++i)
 #pragma unroll
@@ -304,7 +309,8 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__r
 }
 
 template <int DH, int KVSPLIT>
-hipError_t launch_split(hipStream_t stream, const void *qkv, void *out, int B, int L, int H)
+hipError_t launch_split(hipStream_t stream, const void *q, const void *kv, void *out, int B, int Lk, int H,
+                        const SeqRows &rows, int max_count)
 {
     constexpr int QT = 128 / KVSPLIT;
     const size_t lds = sizeof(Smem<DH, KVSPLIT>);
@@ -318,27 +324,52 @@ hipError_t launch_split(hipStream_t stream, const void *qkv, void *out, int B, i
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(((L + QT - 1) / QT) * H * B), dim3(kThreads), lds, stream, (const uint16_t *)qkv,
-                       (uint16_t *)out, L, H);
+    const int nq = (max_count + QT - 1) / QT;
+    hipLaunchKernelGGL(kern, dim3(nq * H * B), dim3(kThreads), lds, stream, (const uint16_t *)q, (const uint16_t *)kv,
+                       (uint16_t *)out, Lk, H, nq, rows);
     return hipGetLastError();
 }
 
 template <int DH>
-hipError_t launch_dh(hipStream_t stream, const void *qkv, void *out, int B, int L, int H)
+hipError_t launch_dh(hipStream_t stream, const void *q, const void *kv, void *out, int B, int Lk, int H,
+                     const SeqRows &rows)
 {
+    int max_count = 0;
+    for (int b = 0; b < B; ++b) max_count = rows.count[b] > max_count ? rows.count[b] : max_count;
+    if (max_count == 0) return hipSuccess;
     // few workgroups: split the keys inside a workgroup to shorten the chain
-    const long wgs128 = (long)((L + 127) / 128) * H * B;
-    if (wgs128 < 1024) return launch_split<DH, 2>(stream, qkv, out, B, L, H);
-    return launch_split<DH, 1>(stream, qkv, out, B, L, H);
+    const long wgs128 = (long)((max_count + 127) / 128) * H * B;
+    if (wgs128 < 1024) return launch_split<DH, 2>(stream, q, kv, out, B, Lk, H, rows, max_count);
+    return launch_split<DH, 1>(stream, q, kv, out, B, Lk, H, rows, max_count);
 }
 
 }  // namespace
 
+hipError_t launch_attention_rows(hipStream_t stream, const void *q, const void *kv, void *out, int B, int Lk, int H,
+                                 int dh, const SeqRows &rows)
+{
+    if (B < 1 || B > DLLM_MAX_BATCH) return hipErrorInvalidValue;
+    if (dh == 128) return launch_dh<128>(stream, q, kv, out, B, Lk, H, rows);
+    if (dh == 64) return launch_dh<64>(stream, q, kv, out, B, Lk, H, rows);
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_attention(hipStream_t stream, const void *qkv, void *out, int B, int L, int H, int dh)
 {
-    if (dh == 128) return launch_dh<128>(stream, qkv, out, B, L, H);
-    if (dh == 64) return launch_dh<64>(stream, qkv, out, B, L, H);
-    return hipErrorInvalidValue;
+    if (B <= DLLM_MAX_BATCH) {
+        SeqRows rows;
+        for (int b = 0; b < B; ++b) { rows.first[b] = b * L; rows.count[b] = L; }
+        return launch_attention_rows(stream, qkv, qkv, out, B, L, H, dh, rows);
+    }
+    // more sequences than the row table holds (test hook only): one launch per group
+    for (int b0 = 0; b0 < B; b0 += DLLM_MAX_BATCH) {
+        const int nb = B - b0 < DLLM_MAX_BATCH ? B - b0 : DLLM_MAX_BATCH;
+        const size_t off = (size_t)b0 * L * 3 * H * dh;
+        hipError_t e = launch_attention(stream, (const uint16_t *)qkv + off,
+                                        (uint16_t *)out + (size_t)b0 * L * H * dh, nb, L, H, dh);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace dllm

@@ -33,6 +33,11 @@ struct Workspace {
     int32_t *cl_pos = nullptr, *cl_tok = nullptr;
     float *cl_conf = nullptr;      // [max_batch][max_seq]
     uint8_t *host_pinned = nullptr;
+    // out-of-span caching: per-layer qkv rows of every position (k and v thirds are the cached features)
+    std::vector<uint16_t *> kv_cache;
+    int32_t *rows_d = nullptr, *pos_d = nullptr;  // recomputed rows of a step and their positions, [M]
+    bool cache_valid = false;
+    int cache_B = 0, cache_L = 0;  // batch shape the cache rows belong to
 };
 constexpr int kMaxSplits = 8;
 
@@ -89,7 +94,8 @@ int dev_alloc(dllm_handle *h, T **p, size_t count)
 }
 
 // Checks the per-sequence parameters and turns them into kernel windows.
-int build_select_args(dllm_handle *h, int B, int L, const dllm_stage_params *sp, int capacity, SelectArgs *out)
+int build_select_args(dllm_handle *h, int B, int L, const dllm_stage_params *sp, int capacity, SelectArgs *out,
+                      const int32_t *cache_mode = nullptr)
 {
     if (B < 1 || B > DLLM_MAX_BATCH) return fail(h, DLLM_EINVAL, "batch %d outside [1, %d]", B, DLLM_MAX_BATCH);
     if (L < 1 || L > 8192) return fail(h, DLLM_EINVAL, "sequence length %d outside [1, 8192]", L);
@@ -99,7 +105,12 @@ int build_select_args(dllm_handle *h, int B, int L, const dllm_stage_params *sp,
         SeqWindow &w = out->w[b];
         w.stage = p.stage; w.top_k = p.top_k; w.tau_min = p.tau_min_conf; w.tau_high = p.tau_high_conf;
         w.conv_mode = p.conv_mode;
-        if (p.stage == DLLM_STAGE_IDLE) { w.lo = 0; w.hi = -1; continue; }
+        const int cm = cache_mode ? cache_mode[b] : DLLM_CACHE_OFF;
+        if (cm != DLLM_CACHE_OFF && cm != DLLM_CACHE_REFRESH && cm != DLLM_CACHE_REUSE)
+            return fail(h, DLLM_EINVAL, "sequence %d: unknown cache mode %d", b, cm);
+        if (p.stage == DLLM_STAGE_IDLE) { w.lo = 0; w.hi = -1; w.eval_hi = -1; continue; }
+        if (cm != DLLM_CACHE_OFF && p.stage != DLLM_STAGE_FAST)
+            return fail(h, DLLM_EINVAL, "sequence %d: caching belongs to the fast stage", b);
         if (p.stage != DLLM_STAGE_SLOW && p.stage != DLLM_STAGE_FAST)
             return fail(h, DLLM_EINVAL, "sequence %d: unknown stage %d", b, p.stage);
         if (p.gen_start < 0 || p.gen_end > L || p.gen_start > p.gen_end)
@@ -110,12 +121,14 @@ int build_select_args(dllm_handle *h, int B, int L, const dllm_stage_params *sp,
             return fail(h, DLLM_EINVAL, "sequence %d: conv_mode %d is not 0 or 1", b, p.conv_mode);
         w.lo = p.s_cycle;
         w.hi = p.stage == DLLM_STAGE_SLOW ? p.gen_end - 1 : p.e_cycle;
+        w.eval_hi = cm == DLLM_CACHE_REFRESH ? p.gen_end - 1 : w.hi;  // a refresh step also rates what lies right of the span
         if (p.stage == DLLM_STAGE_FAST && p.e_cycle < p.s_cycle)
             return fail(h, DLLM_EINVAL, "sequence %d: fast stage with e_cycle %d < s_cycle %d", b, p.e_cycle,
                         p.s_cycle);
         if (w.lo < p.gen_start || w.hi >= p.gen_end)
             return fail(h, DLLM_EINVAL, "sequence %d: window [%d, %d] outside the generated region [%d, %d)", b, w.lo,
                         w.hi, p.gen_start, p.gen_end);
+        if (w.eval_hi < w.hi) w.eval_hi = w.hi;
         if (w.hi - w.lo + 1 > longest) longest = w.hi - w.lo + 1;
     }
     if (capacity < longest)
@@ -141,7 +154,7 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const Sele
     const int M = B * L, d = c.d_model, f = c.d_ffn;
     Workspace &w = h->ws;
     hipStream_t st = h->stream;
-    HIP_TRY(h, launch_embed(st, tokens, h->embed, w.x, M, d));
+    HIP_TRY(h, launch_embed(st, tokens, nullptr, h->embed, w.x, M, d));
     int pending = 0;  // fp32 slabs waiting to be added to the residual stream
     for (int l = 0; l < c.n_layers; ++l) {
         HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->attn_norm[l], w.h, M, d, c.rms_eps));
@@ -187,6 +200,89 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const Sele
     return DLLM_OK;
 }
 
+// Forward with out-of-span caching (Section 3.3).  skip (host, [B][L], nullable): positions that are
+// not recomputed; every other position is recomputed from the current tokens, attends to all L positions
+// of its sequence (cached keys/values for the skipped ones) and refreshes its own cache rows.  The
+// vocabulary projection covers rows lo..eval_hi of each window; none of them may be skipped.
+int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const SelectArgs &win, const uint8_t *skip)
+{
+    const dllm_config &c = h->cfg;
+    const int d = c.d_model, f = c.d_ffn;
+    Workspace &w = h->ws;
+    hipStream_t st = h->stream;
+    if (!gemm_qkv_rope_supported(B * L, d, c.head_dim))
+        return fail(h, DLLM_EINVAL, "cached steps need the fused QKV + RoPE kernel (d_model %% 64 == 0)");
+    const size_t Mmax = (size_t)c.max_batch * c.max_seq;
+    if (w.kv_cache.empty()) {
+        int rc = DLLM_OK;
+        std::vector<uint16_t *> bufs(c.n_layers, nullptr);
+        for (int l = 0; l < c.n_layers && rc == DLLM_OK; ++l) rc = dev_alloc(h, &bufs[l], Mmax * 3 * d);
+        if (rc == DLLM_OK) rc = dev_alloc(h, &w.rows_d, Mmax);
+        if (rc == DLLM_OK) rc = dev_alloc(h, &w.pos_d, Mmax);
+        if (rc != DLLM_OK) return rc;
+        w.kv_cache = bufs;
+    }
+    // the recomputed rows, in order, and where each sequence's rows start
+    std::vector<int32_t> rows, pos;
+    rows.reserve((size_t)B * L); pos.reserve((size_t)B * L);
+    SeqRows sr;
+    bool any_skip = false;
+    for (int b = 0; b < B; ++b) {
+        sr.first[b] = (int)rows.size();
+        for (int i = 0; i < L; ++i) {
+            if (skip && skip[(size_t)b * L + i]) { any_skip = true; continue; }
+            rows.push_back(b * L + i);
+            pos.push_back(i);
+        }
+        sr.count[b] = (int)rows.size() - sr.first[b];
+    }
+    const int Ma = (int)rows.size();
+    if (any_skip && !(w.cache_valid && w.cache_B == B && w.cache_L == L))
+        return fail(h, DLLM_ESTATE, "positions are skipped but no step has filled the cache for this batch shape yet");
+    if (Ma == 0) return fail(h, DLLM_EINVAL, "every position is skipped");
+    // pageable source: the runtime stages it before returning, so the vectors may go out of scope
+    HIP_TRY(h, hipMemcpyAsync(w.rows_d, rows.data(), (size_t)Ma * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(w.pos_d, pos.data(), (size_t)Ma * sizeof(int32_t), hipMemcpyHostToDevice, st));
+
+    HIP_TRY(h, launch_embed(st, tokens, w.rows_d, h->embed, w.x, Ma, d));
+    int pending = 0;
+    for (int l = 0; l < c.n_layers; ++l) {
+        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->attn_norm[l], w.h, Ma, d, c.rms_eps));
+        if (!any_skip) {
+            // everything is recomputed: the projection writes straight into the layer's cache
+            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, h->wqkv[l], w.kv_cache[l], Ma, d, c.head_dim, w.rope, L, w.pos_d));
+            HIP_TRY(h, launch_attention_rows(st, w.kv_cache[l], w.kv_cache[l], w.att, B, L, c.n_heads, c.head_dim, sr));
+        } else {
+            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, h->wqkv[l], w.qkv, Ma, d, c.head_dim, w.rope, L, w.pos_d));
+            HIP_TRY(h, launch_scatter_kv(st, w.qkv, w.kv_cache[l], w.rows_d, Ma, d));
+            HIP_TRY(h, launch_attention_rows(st, w.qkv, w.kv_cache[l], w.att, B, L, c.n_heads, c.head_dim, sr));
+        }
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, Ma, d, d));
+        pending = gemm_num_splits(Ma, d, d);
+        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->ffn_norm[l], w.h, Ma, d, c.rms_eps));
+        HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, h->w_gate_up[l], w.act, Ma, 2 * f, d));
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, h->w_down[l], w.partials, Ma, d, f));
+        pending = gemm_num_splits(Ma, d, f);
+    }
+    HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, Ma, d, c.rms_eps));
+    // logits stay indexed by absolute row; the rows of a window are consecutive among the recomputed ones
+    for (int b = 0; b < B; ++b) {
+        const SeqWindow &sw = win.w[b];
+        if (sw.eval_hi < sw.lo) continue;
+        const long first_abs = (long)b * L + sw.lo, n = sw.eval_hi - sw.lo + 1;
+        long first_cmp = sr.first[b];
+        for (int i = 0; i < sw.lo; ++i) first_cmp += !(skip && skip[(size_t)b * L + i]);
+        for (int i = sw.lo; i <= sw.eval_hi; ++i)
+            if (skip && skip[(size_t)b * L + i]) return fail(h, DLLM_EINVAL, "sequence %d: position %d is skipped but inside the window", b, i);
+        HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h + first_cmp * d, h->lm_head, w.logits + first_abs * (long)c.vocab,
+                               (int)n, c.vocab, d));
+    }
+    if (!any_skip) { w.cache_valid = true; w.cache_B = B; w.cache_L = L; }
+    h->last_B = B;
+    h->last_L = L;
+    return DLLM_OK;
+}
+
 int check_batch(dllm_handle *h, int B, int L)
 {
     if (!h) return fail(nullptr, DLLM_EINVAL, "handle is null");
@@ -202,6 +298,8 @@ struct Controller {
     int s_cycle, e_cycle, stage = DLLM_STAGE_SLOW;
     int step_count = 0, steps = 0;
     std::vector<int> hist;
+    int fast_steps = 0;           // steps taken in the current fast stage
+    std::vector<uint8_t> skip;    // cached set of the current fast stage ([L], empty: none)
 
     Controller(int gs, int ge, const dllm_decode_params *pp)
         : gen_start(gs), gen_end(ge), p(pp), s_cycle(gs), e_cycle(ge - 1) {}
@@ -227,7 +325,13 @@ struct Controller {
         sp->top_k = stage == DLLM_STAGE_SLOW ? p->k_slow : p->k_fast;
         return true;
     }
-    void start_slow() { stage = DLLM_STAGE_SLOW; hist.clear(); step_count = 0; }
+    void start_slow() { stage = DLLM_STAGE_SLOW; hist.clear(); step_count = 0; fast_steps = 0; skip.clear(); }
+    // cache mode of the step `next` describes
+    int cache_mode() const
+    {
+        if (stage != DLLM_STAGE_FAST || !p->out_of_span_cache) return DLLM_CACHE_OFF;
+        return fast_steps == 0 ? DLLM_CACHE_REFRESH : DLLM_CACHE_REUSE;
+    }
     void enter_fast(int e, const uint8_t *mask)
     {
         if (e < s_cycle) e = s_cycle;
@@ -235,12 +339,15 @@ struct Controller {
         e_cycle = e;
         if (any_mask(mask, s_cycle, e)) {
             stage = DLLM_STAGE_FAST;
+            fast_steps = 0;
+            skip.clear();
         } else {  // nothing left in the span: the next cycle starts behind it
             s_cycle = e + 1;
             start_slow();
         }
     }
-    void observe(int e_cand, int first_masked, const uint8_t *mask_after)
+    // conf: the step's confidences of this sequence (read after a refresh step only, may be null otherwise)
+    void observe(int e_cand, int first_masked, const uint8_t *mask_after, const float *conf = nullptr)
     {
         ++steps;
         if (stage == DLLM_STAGE_SLOW) {
@@ -258,9 +365,18 @@ struct Controller {
                 enter_fast((int)(sum / (long)hist.size()), mask_after);  // floor of the mean (eq. 8)
             else if (step_count >= p->k_max)
                 enter_fast(e_k, mask_after);  // no convergence: last candidate
-        } else if (!any_mask(mask_after, s_cycle, e_cycle)) {
-            s_cycle = e_cycle + 1;
-            start_slow();
+        } else {
+            if (p->out_of_span_cache && fast_steps == 0 && conf) {
+                // Out-of-span caching: masked, right of the span, below tau_min in this complete step
+                skip.assign(gen_end, 0);
+                for (int i = e_cycle + 1; i < gen_end; ++i)
+                    skip[i] = mask_after[i] && conf[i] < p->tau_min_conf;
+            }
+            ++fast_steps;
+            if (!any_mask(mask_after, s_cycle, e_cycle)) {
+                s_cycle = e_cycle + 1;
+                start_slow();
+            }
         }
     }
 };
@@ -392,6 +508,48 @@ int dllm_step(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *ma
     return DLLM_OK;
 }
 
+int dllm_step_cached(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *mask, int32_t *prev_pred,
+                     const dllm_stage_params *sp, const int32_t *cache_mode, const uint8_t *skip,
+                     const dllm_commit_list *out)
+{
+    int rc = check_batch(h, B, L);
+    if (rc) return rc;
+    if (!tokens || !mask || !prev_pred || !sp || !cache_mode) return fail(h, DLLM_EINVAL, "dllm_step_cached: null argument");
+    CommitOut co;
+    if ((rc = check_commit_list(h, out, &co))) return rc;
+    SelectArgs args;
+    if ((rc = build_select_args(h, B, L, sp, out->capacity, &args, cache_mode))) return rc;
+    bool any_cache = false, any_reuse = false;
+    for (int b = 0; b < B; ++b) {
+        any_cache |= cache_mode[b] != DLLM_CACHE_OFF;
+        any_reuse |= cache_mode[b] == DLLM_CACHE_REUSE;
+    }
+    if (any_reuse && !skip) return fail(h, DLLM_EINVAL, "dllm_step_cached: a sequence reuses the cache but skip is null");
+    if (!any_cache) {
+        if ((rc = forward_impl(h, B, L, tokens, &args))) return rc;
+    } else {
+        // only sequences in reuse mode skip anything
+        std::vector<uint8_t> eff;
+        if (any_reuse) {
+            eff.assign((size_t)B * L, 0);
+            for (int b = 0; b < B; ++b) {
+                if (cache_mode[b] != DLLM_CACHE_REUSE) continue;
+                for (int i = 0; i < L; ++i) {
+                    const uint8_t v = skip[(size_t)b * L + i];
+                    if (v && i <= sp[b].e_cycle)
+                        return fail(h, DLLM_EINVAL, "dllm_step_cached: sequence %d skips position %d, which is not right of its span", b, i);
+                    eff[(size_t)b * L + i] = v != 0;
+                }
+            }
+        }
+        if ((rc = forward_cached_impl(h, B, L, tokens, args, any_reuse ? eff.data() : nullptr))) return rc;
+    }
+    HIP_TRY(h, launch_row_phase(h->stream, h->ws.logits, B, L, h->cfg.vocab, h->cfg.mask_id, mask, args, h->ws.pred,
+                                h->ws.conf));
+    HIP_TRY(h, launch_seq_phase(h->stream, B, L, tokens, mask, prev_pred, h->ws.pred, h->ws.conf, args, co));
+    return DLLM_OK;
+}
+
 int dllm_select(void *hip_stream, const void *logits, int32_t B, int32_t L, int32_t V, int32_t mask_id,
                 int32_t *tokens, uint8_t *mask, int32_t *prev_pred, const dllm_stage_params *sp, int32_t *pred,
                 float *conf, const dllm_commit_list *out)
@@ -422,6 +580,8 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
     if (p->max_steps < 0 || p->k_max < 1 || p->w_hist < 1 || p->k_slow < 1 || p->k_fast < 1)
         return fail(h, DLLM_EINVAL, "dllm_decode: max_steps >= 0, k_max, w_hist, k_slow, k_fast >= 1 required");
     if (p->conv_mode != 0 && p->conv_mode != 1) return fail(h, DLLM_EINVAL, "dllm_decode: conv_mode must be 0 or 1");
+    if (p->out_of_span_cache != 0 && p->out_of_span_cache != 1)
+        return fail(h, DLLM_EINVAL, "dllm_decode: out_of_span_cache must be 0 or 1");
     if (stats && stats_capacity < 0) return fail(h, DLLM_EINVAL, "dllm_decode: negative stats_capacity");
 
     Workspace &w = h->ws;
@@ -443,6 +603,9 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
     std::vector<Controller> ctl;
     for (int b = 0; b < B; ++b) ctl.emplace_back(gen_start, L, p);
     std::vector<dllm_stage_params> sps(B);
+    std::vector<int32_t> modes(B, DLLM_CACHE_OFF);
+    std::vector<uint8_t> skip((size_t)B * L, 0);
+    std::vector<float> hconf(p->out_of_span_cache ? (size_t)B * L : 0);
     int steps = 0;
     for (;;) {
         bool live = false;
@@ -455,17 +618,34 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
         }
         if (!live) break;
         const bool timed = stats && steps < stats_capacity;
+        bool any_cache = false, any_refresh = false;
+        for (int b = 0; b < B; ++b) {
+            modes[b] = sps[b].stage == DLLM_STAGE_IDLE ? DLLM_CACHE_OFF : ctl[b].cache_mode();
+            any_cache |= modes[b] != DLLM_CACHE_OFF;
+            any_refresh |= modes[b] == DLLM_CACHE_REFRESH;
+            if (modes[b] == DLLM_CACHE_REUSE && !ctl[b].skip.empty())
+                memcpy(skip.data() + (size_t)b * L, ctl[b].skip.data(), L);
+            else
+                memset(skip.data() + (size_t)b * L, 0, L);
+        }
         if (timed) HIP_TRY(h, hipEventRecord(h->ev0, st));
-        if ((rc = dllm_step(h, B, L, tokens, mask, w.prev_pred, sps.data(), &cl))) return rc;
+        if (any_cache) {
+            if ((rc = dllm_step_cached(h, B, L, tokens, mask, w.prev_pred, sps.data(), modes.data(), skip.data(), &cl))) return rc;
+        } else {
+            if ((rc = dllm_step(h, B, L, tokens, mask, w.prev_pred, sps.data(), &cl))) return rc;
+        }
         if (timed) HIP_TRY(h, hipEventRecord(h->ev1, st));
         HIP_TRY(h, hipMemcpyAsync(hmask, mask, (size_t)B * L, hipMemcpyDeviceToHost, st));
         HIP_TRY(h, hipMemcpyAsync(hints, w.cl_ints, (size_t)4 * mb * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        if (any_refresh)  // the confidences decide what is cached for the rest of the stage
+            HIP_TRY(h, hipMemcpyAsync(hconf.data(), w.conf, (size_t)B * L * sizeof(float), hipMemcpyDeviceToHost, st));
         HIP_TRY(h, hipStreamSynchronize(st));
         int committed = 0;
         for (int b = 0; b < B; ++b) {
             if (sps[b].stage == DLLM_STAGE_IDLE) continue;
             committed += hints[b];
-            ctl[b].observe(hints[mb + b], hints[2 * mb + b], hmask + (size_t)b * L);
+            ctl[b].observe(hints[mb + b], hints[2 * mb + b], hmask + (size_t)b * L,
+                           modes[b] == DLLM_CACHE_REFRESH ? hconf.data() + (size_t)b * L : nullptr);
         }
         if (timed) {
             float ms = 0.0f;

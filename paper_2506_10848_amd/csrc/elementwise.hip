@@ -11,16 +11,28 @@ constexpr int kThreads = 256;
 
 // x[r][:] = float(E[tokens[r]][:]); d % 8 == 0.
 __global__ __launch_bounds__(kThreads) void embed_kernel(const int32_t *__restrict__ tokens,
+                                                         const int32_t *__restrict__ rows,
                                                          const uint16_t *__restrict__ E, float *__restrict__ x, int d)
 {
     const int r = blockIdx.x;
-    const uint4 *src = reinterpret_cast<const uint4 *>(E + (size_t)tokens[r] * d);
+    const uint4 *src = reinterpret_cast<const uint4 *>(E + (size_t)tokens[rows ? rows[r] : r] * d);
     float4 *dst = reinterpret_cast<float4 *>(x + (size_t)r * d);
     for (int c = threadIdx.x; c < d / 8; c += kThreads) {
         const uint4 q = src[c];
         dst[2 * c] = make_float4(bf16_lo(q.x), bf16_hi(q.x), bf16_lo(q.y), bf16_hi(q.y));
         dst[2 * c + 1] = make_float4(bf16_lo(q.z), bf16_hi(q.z), bf16_lo(q.w), bf16_hi(q.w));
     }
+}
+
+// dst[rows[r]][d .. 3d) = src[r][d .. 3d), rows of 3d bf16; d % 8 == 0.
+__global__ __launch_bounds__(kThreads) void scatter_kv_kernel(const uint16_t *__restrict__ src,
+                                                              uint16_t *__restrict__ dst,
+                                                              const int32_t *__restrict__ rows, int d)
+{
+    const int r = blockIdx.x;
+    const uint4 *s = reinterpret_cast<const uint4 *>(src + (size_t)r * 3 * d + d);
+    uint4 *t = reinterpret_cast<uint4 *>(dst + (size_t)rows[r] * 3 * d + d);
+    for (int c = threadIdx.x; c < 2 * d / 8; c += kThreads) t[c] = s[c];
 }
 
 // x += sum_s partials[s];  h = bf16( x * rsqrt(mean(x^2) + eps) * gain ).  d % 4 == 0.
@@ -118,9 +130,18 @@ __global__ __launch_bounds__(kThreads) void rope_kernel(uint16_t *__restrict__ q
 
 }  // namespace
 
-hipError_t launch_embed(hipStream_t stream, const int32_t *tokens, const void *embed, float *x, int M, int d)
+hipError_t launch_embed(hipStream_t stream, const int32_t *tokens, const int32_t *rows, const void *embed, float *x,
+                        int M, int d)
 {
-    hipLaunchKernelGGL(embed_kernel, dim3(M), dim3(kThreads), 0, stream, tokens, (const uint16_t *)embed, x, d);
+    hipLaunchKernelGGL(embed_kernel, dim3(M), dim3(kThreads), 0, stream, tokens, rows, (const uint16_t *)embed, x, d);
+    return hipGetLastError();
+}
+
+hipError_t launch_scatter_kv(hipStream_t stream, const void *src, void *dst, const int32_t *rows, int n_rows, int d)
+{
+    if (n_rows < 1) return hipSuccess;
+    hipLaunchKernelGGL(scatter_kv_kernel, dim3(n_rows), dim3(kThreads), 0, stream, (const uint16_t *)src,
+                       (uint16_t *)dst, rows, d);
     return hipGetLastError();
 }
 

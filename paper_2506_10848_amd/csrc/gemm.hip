@@ -117,6 +117,7 @@ __device__ __forceinline__ void tile_of(int pid, int num_m, int num_n, int &pid_
 // rounding; pos = row % L, table[pos][j] = (cos, sin) of pos * theta^(-2j/dh).
 struct RopeArgs {
     const float2 *table;
+    const int32_t *pos;  // nullable: position of every row (rows of a gathered subset)
     int L, rope_cols;
 };
 constexpr int kEpiRope64 = 3, kEpiRope128 = 4;  // head_dim is a compile-time constant of the epilogue
@@ -185,7 +186,7 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row = m0 + wm * WTM + i * 32 + l32;
-            const float2 *trow = rope.table + (size_t)(row % rope.L) * HD;
+            const float2 *trow = rope.table + (size_t)(rope.pos ? rope.pos[min(row, M - 1)] : row % rope.L) * HD;
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -340,7 +341,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
     } while (0)
 
     // every kernel argument the epilogue needs is in registers before the loop (see the file header)
-    asm volatile("" ::"s"(Cout), "s"(M), "s"(N), "s"(rope.table), "s"(rope.L), "s"(rope.rope_cols));
+    asm volatile("" ::"s"(Cout), "s"(M), "s"(N), "s"(rope.table), "s"(rope.pos), "s"(rope.L), "s"(rope.rope_cols));
 
 #pragma unroll
     for (int s = 0; s < P; ++s)
@@ -576,7 +577,7 @@ Plan make_plan(int epi, int M, int N, int K)
 
 template <int BM, int BN, int WM, int WN, int BK, int NST, int EPI>
 hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *W, void *C, int M, int N, int K,
-                      int splits, RopeArgs rope = RopeArgs{nullptr, 1, 0})
+                      int splits, RopeArgs rope = RopeArgs{nullptr, nullptr, 1, 0})
 {
     constexpr int BN_OUT = epi_paired(EPI) ? BN / 2 : BN;
     const int n_lim = epi_paired(EPI) ? N / 2 : N;
@@ -615,7 +616,7 @@ hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *
 
 template <int EPI>
 hipError_t dispatch(hipStream_t stream, Plan p, const void *A, const void *W, void *C, int M, int N, int K,
-                    RopeArgs rope = RopeArgs{nullptr, 1, 0})
+                    RopeArgs rope = RopeArgs{nullptr, nullptr, 1, 0})
 {
     switch (p.cfg) {
     case 0:
@@ -642,9 +643,9 @@ bool gemm_qkv_rope_supported(int M, int d, int dh)
 }
 
 hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
-                                const float2 *table, int L)
+                                const float2 *table, int L, const int32_t *pos)
 {
-    const RopeArgs rope{table, L, 2 * d};
+    const RopeArgs rope{table, pos, L, 2 * d};
     const Plan p = make_plan(dh == 128 ? kEpiRope128 : kEpiRope64, M, 3 * d, d);
     if (dh == 128) return dispatch<kEpiRope128>(stream, p, A, W, C, M, 3 * d, d, rope);
     return dispatch<kEpiRope64>(stream, p, A, W, C, M, 3 * d, d, rope);

@@ -11,7 +11,8 @@ namespace dllm {
 
 // Window and rule of one sequence for one step, as the kernels want it.
 struct SeqWindow {
-    int lo, hi;  // inclusive span of positions the step looks at (hi < lo: nothing)
+    int lo, hi;  // inclusive span of positions the step decides on (hi < lo: nothing)
+    int eval_hi; // masked positions in [lo, eval_hi] get a prediction and a confidence (>= hi)
     int stage;
     int top_k;
     float tau_min, tau_high;
@@ -33,13 +34,24 @@ hipError_t launch_seq_phase(hipStream_t stream, int B, int L, int32_t *tokens, u
                             const int32_t *pred, const float *conf, const SelectArgs &args, const CommitOut &out);
 
 // ---- forward pass -------------------------------------------------------------
-hipError_t launch_embed(hipStream_t stream, const int32_t *tokens, const void *embed, float *x, int M, int d);
+// rows (nullable): x[r] is the embedding of tokens[rows[r]] instead of tokens[r]
+hipError_t launch_embed(hipStream_t stream, const int32_t *tokens, const int32_t *rows, const void *embed, float *x,
+                        int M, int d);
+// dst[rows[r]][d .. 3d) = src[r][d .. 3d): the k and v thirds of recomputed rows go to their cache rows
+hipError_t launch_scatter_kv(hipStream_t stream, const void *src, void *dst, const int32_t *rows, int n_rows, int d);
 hipError_t launch_add_rmsnorm(hipStream_t stream, float *x, const float *partials, int n_partials, const void *gain,
                               void *h, int M, int d, float eps);
 hipError_t launch_rope_table(hipStream_t stream, float2 *table, int max_pos, int dh, float theta);
 // table may be null: angles are then computed in the kernel (slow; test hook)
 hipError_t launch_rope(hipStream_t stream, void *qkv, const float2 *table, int B, int L, int H, int dh, float theta);
 hipError_t launch_attention(hipStream_t stream, const void *qkv, void *out, int B, int L, int H, int dh);
+// Queries of sequence b are the rows [first[b], first[b] + count[b]) of q (row stride 3d, q third);
+// it attends to the Lk rows of kv that start at row b * Lk (k and v thirds); out rows as q rows.
+struct SeqRows {
+    int first[DLLM_MAX_BATCH], count[DLLM_MAX_BATCH];
+};
+hipError_t launch_attention_rows(hipStream_t stream, const void *q, const void *kv, void *out, int B, int Lk, int H,
+                                 int dh, const SeqRows &rows);
 
 enum GemmEpilogue {
     kEpiBf16 = 0,     // C bf16 [M][N]
@@ -51,8 +63,9 @@ int gemm_num_splits(int M, int N, int K);
 // QKV projection with the rotary embedding of the q and k thirds fused into the
 // epilogue: C bf16 [M][3d] = A[M][d] * W[3d][d]^T, rows are positions row % L.
 bool gemm_qkv_rope_supported(int M, int d, int dh);
+// pos (nullable): position of every row; default row % L.
 hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
-                                const float2 *table, int L);
+                                const float2 *table, int L, const int32_t *pos = nullptr);
 // C = A[M][K] * W[N][K]^T.  For kEpiSwiglu N counts gate + up rows.
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
                        int K);

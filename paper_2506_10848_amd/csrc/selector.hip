@@ -114,7 +114,7 @@ __global__ __launch_bounds__(kRowThreads) void row_phase_kernel(const uint16_t *
     const int r = blockIdx.x;
     const int b = r / L, i = r - b * L;
     const SeqWindow w = args.w[b];
-    if (i < w.lo || i > w.hi || mask[r] == 0) return;  // uniform over the block
+    if (i < w.lo || i > w.eval_hi || mask[r] == 0) return;  // uniform over the block
 
     const uint16_t *row = logits + (size_t)r * V;
     const int tid = threadIdx.x;
@@ -216,6 +216,7 @@ __global__ __launch_bounds__(kSeqThreads) void seq_phase_kernel(int L, int32_t *
         const bool m = mask[row0 + i] != 0;
         my_masks += m;
         flag[i] = 0;
+        if (m && i > w.hi && i <= w.eval_hi) prev_pred[row0 + i] = pred[row0 + i];  // evaluated, not decided on
         if (m && i >= w.lo && i <= w.hi) {
             const float c = conf[row0 + i];
             const int p = pred[row0 + i];

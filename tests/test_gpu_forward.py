@@ -285,3 +285,99 @@ def test_forward_llada8b_all_layers_sampled_rows():
     # never rounds: the stated 2e-2 bar is held per tensor and at each row's arg max logit, not per row.
     logits_close(got, ref, rowwise=False)
     m.close()
+
+
+# ---- out-of-span caching: the forward that reuses cached keys/values ---------------
+
+def run_cached_forward(cfg, batch, span, std=0.02):
+    """A refresh step, some commits inside the span, then a reuse step that skips most masked
+    positions right of the span; returns (library logits, oracle logits) of both steps on the
+    rows each step projects onto the vocabulary."""
+    b = binding()
+    w = synth.make_weights(cfg, std=std)
+    mc = synth.model_config(cfg)
+    tokens, mask, prev = synth.make_state(cfg, batch=batch)
+    wd = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in w.items()}
+    B, L = tokens.shape
+    P = cfg["prompt"]
+    s, e = P, P + span - 1
+    model = b.Model(mc, wd, B, L)
+    out = b.CommitList(B, L)
+    sps = [b.stage_params(b.STAGE_FAST, s, e, 1, 0.1, 0.9, 0, P, L) for _ in range(B)]
+    g_tok, g_mask, g_prev = tokens.to(DEV), mask.to(DEV), prev.to(DEV)
+    snap_tok = tokens.numpy().copy()
+    model.step_cached(g_tok, g_mask, g_prev, sps, [b.CACHE_REFRESH] * B, None, out)
+    torch.cuda.synchronize()
+    rows1 = np.concatenate([np.arange(q * L + s, q * L + L) for q in range(B)])
+    got1 = f64(model.debug_logits(B * L))[rows1]
+    cache = oracle.KVCache(mc, B, L)
+    ref1 = oracle.forward_cached(mc, weights_bits(w), snap_tok, cache, rows1)
+
+    # the state moves on: half of the span gets committed (seeded ids), everything else stays
+    rng = np.random.default_rng(7)
+    tok2 = snap_tok.copy()
+    mask2 = mask.numpy().copy()
+    for q in range(B):
+        tok2[q, s:s + span // 2] = rng.integers(0, cfg["mask_id"], span // 2)
+        mask2[q, s:s + span // 2] = 0
+    skip = np.zeros((B, L), np.uint8)
+    skip[:, e + 1:] = 1
+    skip[:, e + 3::5] = 0                      # a few positions right of the span stay live
+    skip[0, L - 1] = 0
+    g_tok, g_mask = torch.from_numpy(tok2).to(DEV), torch.from_numpy(mask2).to(DEV)
+    model.step_cached(g_tok, g_mask, g_prev, sps, [b.CACHE_REUSE] * B, skip, out)
+    torch.cuda.synchronize()
+    rows2 = np.concatenate([np.arange(q * L + s, q * L + e + 1) for q in range(B)])
+    got2 = f64(model.debug_logits(B * L))[rows2]
+    ref2 = oracle.forward_cached(mc, weights_bits(w), tok2, cache, rows2, skip)
+    fresh2 = oracle.forward(mc, weights_bits(w), tok2, rows=rows2)
+    model.close()
+    return (got1, ref1), (got2, ref2, fresh2)
+
+
+def test_cached_forward_tiny_config():
+    cfg = synth.CONFIGS["tiny"]
+    (g1, r1), (g2, r2, fresh) = run_cached_forward(cfg, 2, span=12, std=0.06)
+    logits_close(g1, r1)
+    logits_close(g2, r2)
+    # the reuse step is an approximation of the full forward, and the library follows the oracle's
+    # approximation, not the exact result
+    assert np.abs(r2 - fresh).max() > 4 * np.abs(g2 - r2).max()
+
+
+def test_cached_forward_medium_config():
+    cfg = synth.CONFIGS["medium"]
+    (g1, r1), (g2, r2, fresh) = run_cached_forward(cfg, 2, span=40)
+    logits_close(g1, r1)
+    logits_close(g2, r2)
+
+
+def test_step_cached_argument_checks():
+    b = binding()
+    cfg = synth.CONFIGS["tiny"]
+    w = synth.make_weights(cfg)
+    wd = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in w.items()}
+    tokens, mask, prev = (t.to(DEV) for t in synth.make_state(cfg, batch=1))
+    B, L = tokens.shape
+    P = cfg["prompt"]
+    model = b.Model(synth.model_config(cfg), wd, B, L)
+    out = b.CommitList(B, L)
+    fast = [b.stage_params(b.STAGE_FAST, P, P + 7, 1, 0.1, 0.9, 0, P, L)]
+    slow = [b.stage_params(b.STAGE_SLOW, P, L - 1, 1, 0.1, 0.9, 0, P, L)]
+    skip = np.zeros((B, L), np.uint8); skip[0, P + 8:] = 1
+    with pytest.raises(b.DllmError):            # nothing cached yet
+        model.step_cached(tokens, mask, prev, fast, [b.CACHE_REUSE], skip, out)
+    with pytest.raises(b.DllmError):            # caching belongs to the fast stage
+        model.step_cached(tokens, mask, prev, slow, [b.CACHE_REFRESH], None, out)
+    with pytest.raises(b.DllmError):            # reuse needs a skip array
+        model.step_cached(tokens, mask, prev, fast, [b.CACHE_REUSE], None, out)
+    with pytest.raises(b.DllmError):
+        model.step_cached(tokens, mask, prev, fast, [7], None, out)
+    model.step_cached(tokens, mask, prev, fast, [b.CACHE_REFRESH], None, out)
+    bad = skip.copy(); bad[0, P + 3] = 1        # inside the span
+    with pytest.raises(b.DllmError):
+        model.step_cached(tokens, mask, prev, fast, [b.CACHE_REUSE], bad, out)
+    model.step_cached(tokens, mask, prev, fast, [b.CACHE_REUSE], skip, out)
+    model.step_cached(tokens, mask, prev, fast, [b.CACHE_OFF], None, out)      # plain step through the same entry
+    torch.cuda.synchronize()
+    model.close()
