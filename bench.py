@@ -245,6 +245,31 @@ def main():
             "tokens_per_fast_step": sum(fast_commits) / max(len(fast_commits), 1),
             "params": f"tau_min = median ({tau_min_q:.3e}), tau_high = 90th percentile ({tau_high_q:.3e}) of the first "
                       "step's confidences, K_max 8, W_hist 2, sigma2 1.0, k_slow=k_fast=1, conv_mode 0"}
+        # fast-stage steps over a 32-token span, without and with out-of-span caching: every masked
+        # position right of the span is cached (random-init confidences are all below tau_min = 0.1)
+        span = min(32, G)
+        fsp = [b.stage_params(b.STAGE_FAST, P, P + span - 1, 1, 0.1, 0.9, 0, P, L) for _ in range(B)]
+        import numpy as np
+        skip = np.zeros((B, L), np.uint8)
+        skip[:, P + span:] = 1
+
+        def timed_steps(fn, n=6):
+            tk, mk, pv = tokens0.clone(), mask0.clone(), prev0.clone()
+            fn(tk, mk, pv)                       # warm-up (and, for the cached variants, the cache fill)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(n):
+                fn(tk, mk, pv)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) * 1e3 / n
+
+        plain_ms = timed_steps(lambda tk, mk, pv: model.step(tk, mk, pv, fsp, out))
+        refresh_ms = timed_steps(lambda tk, mk, pv: model.step_cached(tk, mk, pv, fsp, [b.CACHE_REFRESH] * B, None, out))
+        reuse_ms = timed_steps(lambda tk, mk, pv: model.step_cached(tk, mk, pv, fsp, [b.CACHE_REUSE] * B, skip, out))
+        result["fast_step_out_of_span_cache"] = {
+            "span": span, "rows_total": B * L, "rows_recomputed_in_reuse_step": int(B * L - skip.sum()),
+            "plain_fast_step_ms": plain_ms, "refresh_step_ms": refresh_ms, "reuse_step_ms": reuse_ms,
+            "note": "reuse steps recompute prompt + span only and read cached keys/values for the rest"}
         result["cpu_baseline"] = cpu_baseline_step(mc, weights, tokens0)
         model.close()
         del model, weights

@@ -330,6 +330,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
 
     const int sw = BK == 64 ? ((l32 >> 1) & 7) : ((l32 >> 2) & 3);
     const int a_base = (wm * WTM + l32) * CPR, b_base = (BM + wn * WTN + l32) * CPR;  // uint4 index of fragment 0's row
+    // 32-row sub-tiles of this wave that hold at least one real row: the MFMAs of the others are
+    // skipped (a ragged last M tile then costs its workgroups only the copies, and the chip is
+    // power limited, so the cycles and the energy go to the tiles that have rows)
+    // (not in the 256x256 tile, whose 256 accumulator registers leave no room for one more value)
+    constexpr bool kSkipEmpty = BM * BN < 256 * 256;
+    const int tm_valid = kSkipEmpty ? __builtin_amdgcn_readfirstlane(min(TM, max(0, (M - m0 - wm * WTM + 31) / 32))) : TM;
     bf16x8 af[2][TM], bfr[2][TN];
     // fragments are read in the order of their first use by the MFMA sequence (i outer, j inner):
     // A0, W0 .. W(TN-1), A1 .. A(TM-1)
@@ -388,8 +394,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
 #pragma unroll
                         for (int c = c0 + m * NC / NMF; c < c0 + (m + 1) * NC / NMF; ++c) DLLM_COPY(c, kt + P, cslot);
                     }
-                    acc[m / TN][m % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][m % TN], af[cur][m / TN],
-                                                                                 acc[m / TN][m % TN], 0, 0, 0);
+                    if (!kSkipEmpty || m / TN < tm_valid)
+                        acc[m / TN][m % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][m % TN], af[cur][m / TN],
+                                                                                     acc[m / TN][m % TN], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);  // keeps the hand-made interleaving
                 }
             }
