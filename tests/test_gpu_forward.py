@@ -289,7 +289,7 @@ def test_forward_llada8b_all_layers_sampled_rows():
 
 # ---- out-of-span caching: the forward that reuses cached keys/values ---------------
 
-def run_cached_forward(cfg, batch, span, std=0.02):
+def run_cached_forward(cfg, batch, span, std=0.02, sample=None):
     """A refresh step, some commits inside the span, then a reuse step that skips most masked
     positions right of the span; returns (library logits, oracle logits) of both steps on the
     rows each step projects onto the vocabulary."""
@@ -309,7 +309,9 @@ def run_cached_forward(cfg, batch, span, std=0.02):
     model.step_cached(g_tok, g_mask, g_prev, sps, [b.CACHE_REFRESH] * B, None, out)
     torch.cuda.synchronize()
     rows1 = np.concatenate([np.arange(q * L + s, q * L + L) for q in range(B)])
-    got1 = f64(model.debug_logits(B * L))[rows1]
+    if sample:                                   # full-size shapes: the oracle projects a sample of the rows
+        rows1 = np.sort(np.random.default_rng(3).choice(rows1, sample, replace=False))
+    got1 = f64(model.debug_logits(B * L)[torch.as_tensor(rows1, device=DEV)])
     cache = oracle.KVCache(mc, B, L)
     ref1 = oracle.forward_cached(mc, weights_bits(w), snap_tok, cache, rows1)
 
@@ -328,7 +330,9 @@ def run_cached_forward(cfg, batch, span, std=0.02):
     model.step_cached(g_tok, g_mask, g_prev, sps, [b.CACHE_REUSE] * B, skip, out)
     torch.cuda.synchronize()
     rows2 = np.concatenate([np.arange(q * L + s, q * L + e + 1) for q in range(B)])
-    got2 = f64(model.debug_logits(B * L))[rows2]
+    if sample:
+        rows2 = np.sort(np.random.default_rng(4).choice(rows2, min(sample, len(rows2)), replace=False))
+    got2 = f64(model.debug_logits(B * L)[torch.as_tensor(rows2, device=DEV)])
     ref2 = oracle.forward_cached(mc, weights_bits(w), tok2, cache, rows2, skip)
     fresh2 = oracle.forward(mc, weights_bits(w), tok2, rows=rows2)
     model.close()
@@ -348,6 +352,15 @@ def test_cached_forward_tiny_config():
 def test_cached_forward_medium_config():
     cfg = synth.CONFIGS["medium"]
     (g1, r1), (g2, r2, fresh) = run_cached_forward(cfg, 2, span=40)
+    logits_close(g1, r1)
+    logits_close(g2, r2)
+
+
+def test_cached_forward_llada8b_shape_two_layers_sampled_rows():
+    """The cached steps in the launch shapes of the benchmark (LLaDA-8B widths, vocabulary, L = 512,
+    288 of 512 rows recomputed in the reuse step), 2 of the 32 layers, sampled rows."""
+    cfg = dict(synth.CONFIGS["llada8b"], n_layers=2)
+    (g1, r1), (g2, r2, fresh) = run_cached_forward(cfg, 1, span=32, sample=5)
     logits_close(g1, r1)
     logits_close(g2, r2)
 
