@@ -51,7 +51,7 @@ enum { DLLM_STAGE_SLOW = 0, DLLM_STAGE_FAST = 1, DLLM_STAGE_IDLE = 2 };
 typedef struct dllm_handle dllm_handle; /* opaque, owned by the library */
 
 /* Shape of the mask predictor.  The paper only calls it a bidirectional
- * Transformer (Section 2.1); the operator stack is LLaDA-style: pre-norm
+ * Transformer (Section 3.1); the operator stack is LLaDA-style: pre-norm
  * RMSNorm, rotate-half RoPE on q and k, non-causal multi-head attention with
  * scale 1/sqrt(head_dim), SwiGLU feed-forward, untied vocabulary projection,
  * no biases.  Requires n_heads * head_dim == d_model, head_dim in {64, 128},
@@ -203,7 +203,7 @@ int dllm_step_cached(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint
 int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t *tokens, uint8_t *mask,
                 const dllm_decode_params *p, int32_t *steps_taken, dllm_step_stat *stats, int32_t stats_capacity);
 
-/* The baseline sampler the method is measured against (Section 2.1, "Low-Confidence
+/* The baseline sampler the method is measured against (Section 3.1, "Low-Confidence
  * Remasking", optionally "Semi-Autoregressive"): the generated region [gen_start, L) is
  * cut into blocks of block_len positions that are denoised left to right with
  * n_steps / (number of blocks) steps each; after the j-th of a block's N_b steps the
@@ -265,7 +265,7 @@ int dllm_op_add_rmsnorm(void *hip_stream, float *x, const float *partials, int32
                         const void *gain, void *h, int32_t M, int32_t d, float eps);
 /* In-place RoPE on the q and k thirds of qkv bf16 [B*L][3*H*dh]. */
 int dllm_op_rope(void *hip_stream, void *qkv, int32_t B, int32_t L, int32_t H, int32_t dh, float theta);
-/* Fused QKV projection + RoPE (Section 2.1's bidirectional transformer block; rotary embedding
+/* Fused QKV projection + RoPE (Section 3.1's bidirectional transformer block; rotary embedding
  * as in LLaDA): qkv bf16 [B*L][3*H*dh] = A[B*L][H*dh] * W[3*H*dh][H*dh]^T with the q and k thirds
  * rotated in fp32 before the single bf16 rounding; row r has position r % L.  `table` is scratch
  * the caller provides, float [L][dh/2][2] dev, filled with (cos, sin) by this call.

@@ -34,7 +34,16 @@ Readings taken where the paper is silent or at odds with itself:
   values in every layer as computed in that step.  The later steps of the
   stage do not recompute them: all other positions are recomputed from the
   current tokens and attend to those cached keys/values.  The set is dropped
-  when the stage ends.  Prompt and committed positions are always recomputed.
+  when the stage ends.  Committed positions are always recomputed, and so is
+  the prompt unless prompt caching is on.
+* Prompt caching (optional, DecodeParams.prompt_cache_interval = K_p > 0), the
+  long-interval half of the dLLM-Cache scheme the paper combines its sampler
+  with (Section 4.2, "Compatibility with dLLM-Cache"), in the simplest form
+  that fits the same cache: every K_p-th step of a decode (counting from 0) is
+  a complete forward that refreshes the keys/values of every position; in the
+  steps between, the prompt positions are not recomputed and everyone attends
+  to their cached keys/values.  The response-side half of that scheme
+  (short-interval refresh with value-based selection) is not modelled.
 """
 from __future__ import annotations
 
@@ -91,6 +100,7 @@ class DecodeParams:
     k_fast: int = 1
     conv_mode: int = 0
     out_of_span_cache: bool = False
+    prompt_cache_interval: int = 0     # K_p; 0 = the prompt is recomputed in every step
 
 
 def active_rows(sp: StageParams, mask: np.ndarray) -> np.ndarray:
@@ -140,23 +150,27 @@ Predictor = Callable[[np.ndarray, np.ndarray], Tuple[np.ndarray, np.ndarray]]
 the greedy estimate and its confidence at the active positions."""
 
 
-def step(predict: Predictor, tokens, mask, prev_pred, sps: Sequence[StageParams], skip=None):
+def step(predict: Predictor, tokens, mask, prev_pred, sps: Sequence[StageParams], skip=None, also_skip=None):
     """One denoising step on a batch, in place.  Returns, per sequence,
     (commit positions, committed tokens, their confidences, e_cand,
     first_masked, masks left in the sequence, the step's confidences).
 
-    With out-of-span caching some sequences carry cache_mode != CACHE_OFF; the
-    predictor must then offer predict.cached(tokens, active, skip) where
-    skip[b, i] != 0 marks the positions of CACHE_REUSE sequences that are not
-    recomputed (it refreshes the cached features of every other position)."""
+    With caching the predictor must offer predict.cached(tokens, active, skip),
+    where skip[b, i] != 0 marks the positions that are not recomputed (it
+    refreshes the cached features of every other position).  skip[b]: the
+    out-of-span set of a CACHE_REUSE sequence.  also_skip [B, L] (prompt
+    caching): further positions to leave out in this step; an all-zero array
+    asks for a complete forward through the cached path (a refresh)."""
     B, L = tokens.shape
     active = np.stack([active_rows(sps[b], mask[b]) for b in range(B)])
-    if any(sp.cache_mode != CACHE_OFF for sp in sps):
+    if any(sp.cache_mode != CACHE_OFF for sp in sps) or also_skip is not None:
         sk = np.zeros((B, L), dtype=np.uint8)
         for b in range(B):
             if sps[b].cache_mode == CACHE_REUSE:
                 sk[b] = skip[b]
-                assert not np.any(sk[b] & active[b]), "a skipped position has no prediction"
+            if also_skip is not None and sps[b].cache_mode != CACHE_REFRESH:
+                sk[b] |= np.asarray(also_skip[b], dtype=np.uint8)
+            assert not np.any(sk[b] & active[b]), "a skipped position has no prediction"
         pred, conf = predict.cached(tokens, active, sk)
     else:
         pred, conf = predict(tokens, active)
@@ -271,7 +285,12 @@ def decode(predict: Predictor, tokens, mask, gen_start: int, gen_end: int, p: De
         if not live:
             return steps
         skip = [ctl[b].skip for b in range(B)]
-        res = step(predict, tokens, mask, prev_pred, sps, skip)
+        also = None
+        if p.prompt_cache_interval > 0:
+            also = np.zeros((B, L), dtype=np.uint8)
+            if steps % p.prompt_cache_interval != 0:
+                also[:, :gen_start] = 1
+        res = step(predict, tokens, mask, prev_pred, sps, skip, also)
         steps += 1
         for b in range(B):
             if sps[b].stage != IDLE:
@@ -281,7 +300,7 @@ def decode(predict: Predictor, tokens, mask, gen_start: int, gen_end: int, p: De
 
 
 def n_unmasked_target(length: int, n_steps: int, j: int) -> int:
-    """Low-confidence remasking schedule (Section 2.1): after the j-th of n_steps
+    """Low-confidence remasking schedule (Section 3.1): after the j-th of n_steps
     steps (the paper's k = n_steps - j + 1, t_{k-1} = (k - 1) / n_steps) the state
     holds floor(length * (1 - t_{k-1})) = floor(length * j / n_steps) unmasked tokens."""
     return (length * j) // n_steps
@@ -289,7 +308,7 @@ def n_unmasked_target(length: int, n_steps: int, j: int) -> int:
 
 def decode_low_confidence(predict: Predictor, tokens, mask, gen_start: int, gen_end: int, n_steps: int,
                           block_len: Optional[int] = None, trace: Optional[list] = None) -> int:
-    """The baseline sampler the paper starts from (Section 2.1): low-confidence
+    """The baseline sampler the paper starts from (Section 3.1): low-confidence
     remasking, optionally semi-autoregressive over blocks of block_len positions
     that are denoised left to right with n_steps / n_blocks steps each.
 

@@ -110,7 +110,7 @@ class SlowFastDriver:
 
 
 class LowConfidenceDriver:
-    """Stage parameters of the baseline sampler (Section 2.1): block by block, the
+    """Stage parameters of the baseline sampler (Section 3.1): block by block, the
     schedule's number of new tokens per step, taken from the oracle's schedule function."""
 
     def __init__(self, B, P, L, n_steps, block_len):
@@ -472,7 +472,7 @@ def test_decode_runs_to_completion(gain, tau_high, k_slow):
 
 @pytest.mark.parametrize("n_steps_div,n_blocks", [(1, 1), (2, 1), (2, 4), (4, 2)])
 def test_decode_low_confidence(n_steps_div, n_blocks):
-    """dllm_decode_low_confidence: the schedule of Section 2.1 (steps taken, tokens per
+    """dllm_decode_low_confidence: the schedule of Section 3.1 (steps taken, tokens per
     step), the end state, and bit-equality with the same schedule driven step by step
     through dllm_step (same kernels, so the host loop is the only difference)."""
     b = binding()

@@ -237,7 +237,7 @@ def test_max_steps_stops_the_decode():
     assert mask.sum() == L - P - 3
 
 
-# ---- low-confidence remasking baseline (Section 2.1) ------------------------------
+# ---- low-confidence remasking baseline (Section 3.1) ------------------------------
 
 def test_low_confidence_schedule_values():
     # n_un = floor(L (1 - (k-1)/N)), k = N .. 1, worked by hand:
@@ -424,3 +424,58 @@ def test_cached_decode_on_a_small_model_keeps_the_invariants():
                 assert len(res[b][0]) >= 1
                 lo, hi = sps[b].window()
                 assert all(lo <= i <= hi for i in res[b][0])
+
+
+# ---- prompt caching (the long-interval half of dLLM-Cache, Section 4.2) -------------
+
+def test_prompt_caching_protocol_and_state_independent_trajectory():
+    rng = np.random.default_rng(21)
+    P, G = 4, 30
+    L = P + G
+    conf = (rng.random((2, L)) ** 3).astype(np.float32)
+    pred = rng.integers(0, 50, (2, L)).astype(np.int32)
+    runs = []
+    for kp, oos in ((0, False), (3, False), (3, True), (1, True)):
+        tokens = np.full((2, L), 99, np.int32); mask = np.zeros((2, L), np.uint8); mask[:, P:] = 1
+        rp = RecordingPredictor(conf, pred)
+        trace = []
+        p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.2, tau_high_conf=0.6, out_of_span_cache=oos,
+                            prompt_cache_interval=kp)
+        steps = sf.decode(rp, tokens, mask, P, L, p, trace)
+        runs.append((steps, [[r[0] for r in res] for _, res in trace], tokens.copy()))
+        if kp:
+            assert all(c[0] == "cached" for c in rp.calls)
+            for n, ((kind, active, skip), (sps, _)) in enumerate(zip(rp.calls, trace)):
+                # every K_p-th step recomputes the prompt, the others leave all of it out (a sequence in an
+                # out-of-span refresh step recomputes everything)
+                for q in range(2):
+                    full = n % kp == 0 or sps[q].cache_mode == sf.CACHE_REFRESH
+                    assert not skip[q, :P].any() if full else skip[q, :P].all()
+                assert not (skip & active).any()
+                if not oos:
+                    assert not skip[:, P:].any()
+    for r in runs[1:]:                                   # predictions do not depend on the state here
+        assert r[0] == runs[0][0] and r[1] == runs[0][1] and np.array_equal(r[2], runs[0][2])
+
+
+def test_prompt_caching_with_interval_one_is_the_plain_decode():
+    from util import OraclePredictor
+    cfg = dict(synth.CONFIGS["tiny"], vocab=257, mask_id=256, prompt=6, gen=16, d_model=64, n_heads=2,
+               head_dim=32, d_ffn=96, n_layers=2)
+    w = synth.make_weights(cfg, std=0.25)
+    outs = []
+    for kp in (0, 1, 4):
+        tokens, mask, _ = synth.make_state(cfg, batch=2)
+        tokens, mask = tokens.numpy().copy(), mask.numpy().copy()
+        B, L = tokens.shape
+        predict = OraclePredictor(synth.model_config(cfg), weights_bits(w), B, L)
+        p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.004, tau_high_conf=0.0045, prompt_cache_interval=kp)
+        trace = []
+        steps = sf.decode(predict, tokens, mask, cfg["prompt"], L, p, trace)
+        assert not mask.any() and not (tokens == cfg["mask_id"]).any()
+        outs.append((steps, tokens.copy(), list(predict.recomputed)))
+    # K_p = 1: every step is a complete forward through the cached path = the plain decode, exactly
+    assert outs[1][0] == outs[0][0] and np.array_equal(outs[1][1], outs[0][1])
+    # K_p = 4: three of four steps leave the prompt out
+    rec = outs[2][2]
+    assert all(n == (B * L if i % 4 == 0 else B * (L - cfg["prompt"])) for i, n in enumerate(rec))
