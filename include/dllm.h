@@ -132,6 +132,10 @@ typedef struct {
                                   a fast stage is a complete prediction; masked positions right of e_cycle whose
                                   confidence there is below tau_min_conf are not recomputed (their keys/values
                                   are reused) in the later steps of that stage */
+    int32_t prompt_cache_interval; /* K_p >= 0.  0: off.  Otherwise the long-interval prompt caching of dLLM-Cache,
+                                      which the paper combines its sampler with (Section 4.2), in its simplest form:
+                                      every K_p-th step (from step 0) is a complete forward that refreshes all cached
+                                      keys/values; in the steps between, the prompt positions are not recomputed */
 } dllm_decode_params;
 
 /* One record per denoising step of dllm_decode. */
@@ -177,14 +181,15 @@ int dllm_step(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *ma
  *   DLLM_CACHE_REUSE    later steps of the stage: positions with skip[b][i] != 0 are not
  *                       recomputed; all others are, attend to the cached keys/values of the
  *                       skipped ones, and refresh their own cache rows
- * REFRESH and REUSE require the fast stage.  In any step with a sequence in REFRESH or REUSE the
+ * REFRESH widens the rated range only in the fast stage; REUSE may skip any position outside the
+ * sequence's window (prompt caching skips the prompt).  In any step with a sequence in REFRESH or REUSE the
  * keys/values of every recomputed position of the batch are written to the cache (allocated on
  * first use: n_layers x max_batch x max_seq x 3 d_model bf16).
  *   cache_mode  host int32 [B]
  *   skip        host uint8 [B][L], may be NULL when no sequence is in REUSE; read before the
- *               call returns; skip[b][i] != 0 requires i > e_cycle of sequence b
+ *               call returns; a skipped position must lie outside the positions the step rates
  * Errors beyond dllm_step's: DLLM_ESTATE when positions are skipped before any step filled the
- * cache; DLLM_EINVAL for a skipped position at or left of e_cycle, or a model whose d_model is
+ * cache; DLLM_EINVAL for a skipped position inside the window, or a model whose d_model is
  * not a multiple of 64 (the cached path uses the fused QKV + RoPE kernel only). */
 #define DLLM_CACHE_OFF 0
 #define DLLM_CACHE_REFRESH 1

@@ -109,8 +109,7 @@ int build_select_args(dllm_handle *h, int B, int L, const dllm_stage_params *sp,
         if (cm != DLLM_CACHE_OFF && cm != DLLM_CACHE_REFRESH && cm != DLLM_CACHE_REUSE)
             return fail(h, DLLM_EINVAL, "sequence %d: unknown cache mode %d", b, cm);
         if (p.stage == DLLM_STAGE_IDLE) { w.lo = 0; w.hi = -1; w.eval_hi = -1; continue; }
-        if (cm != DLLM_CACHE_OFF && p.stage != DLLM_STAGE_FAST)
-            return fail(h, DLLM_EINVAL, "sequence %d: caching belongs to the fast stage", b);
+
         if (p.stage != DLLM_STAGE_SLOW && p.stage != DLLM_STAGE_FAST)
             return fail(h, DLLM_EINVAL, "sequence %d: unknown stage %d", b, p.stage);
         if (p.gen_start < 0 || p.gen_end > L || p.gen_start > p.gen_end)
@@ -121,7 +120,8 @@ int build_select_args(dllm_handle *h, int B, int L, const dllm_stage_params *sp,
             return fail(h, DLLM_EINVAL, "sequence %d: conv_mode %d is not 0 or 1", b, p.conv_mode);
         w.lo = p.s_cycle;
         w.hi = p.stage == DLLM_STAGE_SLOW ? p.gen_end - 1 : p.e_cycle;
-        w.eval_hi = cm == DLLM_CACHE_REFRESH ? p.gen_end - 1 : w.hi;  // a refresh step also rates what lies right of the span
+        // a refresh step of the fast stage also rates what lies right of the span
+        w.eval_hi = (cm == DLLM_CACHE_REFRESH && p.stage == DLLM_STAGE_FAST) ? p.gen_end - 1 : w.hi;
         if (p.stage == DLLM_STAGE_FAST && p.e_cycle < p.s_cycle)
             return fail(h, DLLM_EINVAL, "sequence %d: fast stage with e_cycle %d < s_cycle %d", b, p.e_cycle,
                         p.s_cycle);
@@ -536,8 +536,8 @@ int dllm_step_cached(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint
                 if (cache_mode[b] != DLLM_CACHE_REUSE) continue;
                 for (int i = 0; i < L; ++i) {
                     const uint8_t v = skip[(size_t)b * L + i];
-                    if (v && i <= sp[b].e_cycle)
-                        return fail(h, DLLM_EINVAL, "dllm_step_cached: sequence %d skips position %d, which is not right of its span", b, i);
+                    if (v && i >= args.w[b].lo && i <= args.w[b].eval_hi)
+                        return fail(h, DLLM_EINVAL, "dllm_step_cached: sequence %d skips position %d, which is inside its window", b, i);
                     eff[(size_t)b * L + i] = v != 0;
                 }
             }
@@ -582,6 +582,7 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
     if (p->conv_mode != 0 && p->conv_mode != 1) return fail(h, DLLM_EINVAL, "dllm_decode: conv_mode must be 0 or 1");
     if (p->out_of_span_cache != 0 && p->out_of_span_cache != 1)
         return fail(h, DLLM_EINVAL, "dllm_decode: out_of_span_cache must be 0 or 1");
+    if (p->prompt_cache_interval < 0) return fail(h, DLLM_EINVAL, "dllm_decode: prompt_cache_interval must be >= 0");
     if (stats && stats_capacity < 0) return fail(h, DLLM_EINVAL, "dllm_decode: negative stats_capacity");
 
     Workspace &w = h->ws;
@@ -619,14 +620,23 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
         if (!live) break;
         const bool timed = stats && steps < stats_capacity;
         bool any_cache = false, any_refresh = false;
+        // prompt caching: every K_p-th step recomputes everything, the others leave the prompt out
+        const int kp = p->prompt_cache_interval;
+        const bool prompt_refresh = kp > 0 && steps % kp == 0;
         for (int b = 0; b < B; ++b) {
-            modes[b] = sps[b].stage == DLLM_STAGE_IDLE ? DLLM_CACHE_OFF : ctl[b].cache_mode();
-            any_cache |= modes[b] != DLLM_CACHE_OFF;
-            any_refresh |= modes[b] == DLLM_CACHE_REFRESH;
-            if (modes[b] == DLLM_CACHE_REUSE && !ctl[b].skip.empty())
-                memcpy(skip.data() + (size_t)b * L, ctl[b].skip.data(), L);
+            uint8_t *sk = skip.data() + (size_t)b * L;
+            const int oos = sps[b].stage == DLLM_STAGE_IDLE ? DLLM_CACHE_OFF : ctl[b].cache_mode();
+            any_refresh |= oos == DLLM_CACHE_REFRESH;
+            if (oos == DLLM_CACHE_REUSE && !ctl[b].skip.empty())
+                memcpy(sk, ctl[b].skip.data(), L);
             else
-                memset(skip.data() + (size_t)b * L, 0, L);
+                memset(sk, 0, L);
+            modes[b] = oos;
+            if (kp > 0 && oos != DLLM_CACHE_REFRESH) {
+                if (!prompt_refresh) memset(sk, 1, gen_start);
+                modes[b] = (oos == DLLM_CACHE_REUSE || !prompt_refresh) ? DLLM_CACHE_REUSE : DLLM_CACHE_REFRESH;
+            }
+            any_cache |= modes[b] != DLLM_CACHE_OFF;
         }
         if (timed) HIP_TRY(h, hipEventRecord(h->ev0, st));
         if (any_cache) {
@@ -645,7 +655,7 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
             if (sps[b].stage == DLLM_STAGE_IDLE) continue;
             committed += hints[b];
             ctl[b].observe(hints[mb + b], hints[2 * mb + b], hmask + (size_t)b * L,
-                           modes[b] == DLLM_CACHE_REFRESH ? hconf.data() + (size_t)b * L : nullptr);
+                           any_refresh ? hconf.data() + (size_t)b * L : nullptr);
         }
         if (timed) {
             float ms = 0.0f;

@@ -380,8 +380,6 @@ def test_step_cached_argument_checks():
     skip = np.zeros((B, L), np.uint8); skip[0, P + 8:] = 1
     with pytest.raises(b.DllmError):            # nothing cached yet
         model.step_cached(tokens, mask, prev, fast, [b.CACHE_REUSE], skip, out)
-    with pytest.raises(b.DllmError):            # caching belongs to the fast stage
-        model.step_cached(tokens, mask, prev, slow, [b.CACHE_REFRESH], None, out)
     with pytest.raises(b.DllmError):            # reuse needs a skip array
         model.step_cached(tokens, mask, prev, fast, [b.CACHE_REUSE], None, out)
     with pytest.raises(b.DllmError):
@@ -392,5 +390,11 @@ def test_step_cached_argument_checks():
         model.step_cached(tokens, mask, prev, fast, [b.CACHE_REUSE], bad, out)
     model.step_cached(tokens, mask, prev, fast, [b.CACHE_REUSE], skip, out)
     model.step_cached(tokens, mask, prev, fast, [b.CACHE_OFF], None, out)      # plain step through the same entry
+    # the slow stage may leave the prompt out (prompt caching), but nothing of its window
+    model.step_cached(tokens, mask, prev, slow, [b.CACHE_REFRESH], None, out)
+    pskip = np.zeros((B, L), np.uint8); pskip[0, :P] = 1
+    model.step_cached(tokens, mask, prev, slow, [b.CACHE_REUSE], pskip, out)
+    with pytest.raises(b.DllmError):
+        model.step_cached(tokens, mask, prev, slow, [b.CACHE_REUSE], skip, out)
     torch.cuda.synchronize()
     model.close()

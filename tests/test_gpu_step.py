@@ -90,6 +90,17 @@ class SlowFastDriver:
     def __init__(self, B, P, L, params):
         self.ctl = [sf.Controller(P, L, params) for _ in range(B)]
         self.P, self.L, self.p = P, L, params
+        self.n = 0
+
+    def also(self):
+        """Prompt caching: positions every sequence leaves out in the coming step (None: feature off)."""
+        kp = self.p.prompt_cache_interval
+        if kp <= 0:
+            return None
+        a = np.zeros((len(self.ctl), self.L), np.uint8)
+        if self.n % kp:
+            a[:, :self.P] = 1
+        return a
 
     def next(self, mask):
         sps = []
@@ -101,6 +112,7 @@ class SlowFastDriver:
         return sps
 
     def observe(self, sps, res, mask):
+        self.n += 1
         for s, c in enumerate(self.ctl):
             if sps[s].stage != sf.IDLE:
                 c.observe(res[s][3], res[s][4], mask[s], res[s][6])
@@ -209,11 +221,15 @@ def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9, driv
                               p.gen_start, p.gen_end) for p in sps]
         modes = [p.cache_mode for p in sps]
         skip = drv.skip() if hasattr(drv, "skip") else None
-        if any(modes):
+        also = drv.also() if hasattr(drv, "also") else None
+        if any(modes) or also is not None:
             sk = np.zeros((B, L), np.uint8)
             for s_ in range(B):
                 if modes[s_] == sf.CACHE_REUSE:
                     sk[s_] = skip[s_]
+                if also is not None and modes[s_] != sf.CACHE_REFRESH:
+                    sk[s_] |= also[s_]
+                    modes[s_] = sf.CACHE_REUSE if (sk[s_].any() or modes[s_] == sf.CACHE_REUSE) else sf.CACHE_REFRESH
             model.step_cached(g_tok, g_mask, g_prev, csp, modes, sk, out)
             stats["cached_steps"] = stats.get("cached_steps", 0) + 1
             stats["rows_skipped"] = stats.get("rows_skipped", 0) + int(sk.sum())
@@ -223,7 +239,7 @@ def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9, driv
         g_logits = oracle.bf16_to_f64(bits(model.debug_logits(B * L)))
         got = out.to_host()
         mask_before, prev_before, tok_before = mask.copy(), prev_pred.copy(), tokens.copy()
-        res = sf.step(predict, tokens, mask, prev_pred, sps, skip)
+        res = sf.step(predict, tokens, mask, prev_pred, sps, skip, also)
         last = predict.last
 
         # logits: the stated bar, and the tighter bound the exemption rule relies on
@@ -346,6 +362,17 @@ def test_lockstep_out_of_span_caching_random_init():
     print("lockstep cached, random init:", st)
 
 
+def test_lockstep_prompt_caching():
+    """Prompt caching (K_p = 4) together with out-of-span caching under Algorithm 1's controller:
+    three of four steps recompute the generated region only."""
+    cfg = synth.CONFIGS["tiny"]
+    p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.2, tau_high_conf=0.3, conv_mode=1, k_slow=2,
+                        out_of_span_cache=True, prompt_cache_interval=4)
+    st = lockstep(cfg, 2, p, final_gain=10.0)
+    assert st["cached_steps"] == st["steps"] and st["rows_skipped"] >= (st["steps"] // 2) * 2 * cfg["prompt"]
+    print("lockstep prompt caching:", st)
+
+
 def test_lockstep_low_confidence_baseline():
     """The baseline sampler's steps (top-k of a block by confidence, k from the
     schedule) through the same lock-step protocol: 4 blocks, 2 tokens per step."""
@@ -359,13 +386,13 @@ def test_lockstep_low_confidence_baseline():
 
 def decode_params(b, p: sf.DecodeParams):
     return b.DecodeParams(p.max_steps, p.k_max, p.w_hist, p.k_slow, p.k_fast, p.conv_mode, p.sigma2_stable,
-                          p.tau_min_conf, p.tau_high_conf, int(p.out_of_span_cache))
+                          p.tau_min_conf, p.tau_high_conf, int(p.out_of_span_cache), int(p.prompt_cache_interval))
 
 
-@pytest.mark.parametrize("cache", [False, True])
+@pytest.mark.parametrize("cache,kp", [(False, 0), (True, 0), (True, 3), (False, 5)])
 @pytest.mark.parametrize("gain,tau_min,tau_high,k_max,w_hist", [(10.0, 0.2, 0.3, 8, 2), (10.0, 0.23, 0.999, 1, 1),
                                                                (1.0, None, None, 8, 2)])
-def test_decode_host_controller_matches_the_oracles_controller(cache, gain, tau_min, tau_high, k_max, w_hist):
+def test_decode_host_controller_matches_the_oracles_controller(cache, kp, gain, tau_min, tau_high, k_max, w_hist):
     """dllm_decode's host loop against the oracle's Controller driven by the library's own step
     outputs (same kernels on both sides, so tokens and step counts must be identical): covers the
     stage transitions of Algorithm 1 and the refresh / reuse protocol of out-of-span caching."""
@@ -386,7 +413,7 @@ def test_decode_host_controller_matches_the_oracles_controller(cache, gain, tau_
         c0 = model.debug_rows(B * L)[1].view(B, L)[mask.bool().to(DEV)].float()
         tau_min, tau_high = float(c0.quantile(0.5)), float(c0.quantile(0.9))
     p = sf.DecodeParams(max_steps=10 ** 6, k_max=k_max, w_hist=w_hist, tau_min_conf=tau_min, tau_high_conf=tau_high,
-                        conv_mode=0, k_slow=1, k_fast=1, out_of_span_cache=cache)
+                        conv_mode=0, k_slow=1, k_fast=1, out_of_span_cache=cache, prompt_cache_interval=kp)
     g_tok, g_mask = tokens.to(DEV), mask.to(DEV)
     steps, stats = model.decode(g_tok, g_mask, P, decode_params(b, p), stats_capacity=4 * G)
     assert int(g_mask.sum()) == 0
@@ -404,11 +431,15 @@ def test_decode_host_controller_matches_the_oracles_controller(cache, gain, tau_
         csp = [b.stage_params(x.stage, x.s_cycle, x.e_cycle, x.top_k, x.tau_min_conf, x.tau_high_conf, x.conv_mode,
                               x.gen_start, x.gen_end) for x in sps]
         modes = [x.cache_mode for x in sps]
-        if any(modes):
+        if any(modes) or kp:
             sk = np.zeros((B, L), np.uint8)
             for q in range(B):
                 if modes[q] == sf.CACHE_REUSE:
                     sk[q] = ctl[q].skip
+                if kp and modes[q] != sf.CACHE_REFRESH:
+                    if n % kp:
+                        sk[q, :P] = 1
+                    modes[q] = sf.CACHE_REUSE if (sk[q].any() or modes[q] == sf.CACHE_REUSE) else sf.CACHE_REFRESH
             reuse_rows += int(sk.sum())
             model.step_cached(s_tok, s_mask, s_prev, csp, modes, sk, out)
         else:
@@ -423,7 +454,7 @@ def test_decode_host_controller_matches_the_oracles_controller(cache, gain, tau_
         n += 1
     assert n == steps and torch.equal(s_tok.cpu(), g_tok.cpu())
     print(f"decode cache={cache} gain={gain}: {steps} steps, rows skipped in reuse steps {reuse_rows}")
-    if cache and k_max == 1:       # (confidences sit in 0.20 .. 0.24 here: 0.23 ends the span mid-region)
+    if (cache and k_max == 1) or kp:       # (confidences sit in 0.20 .. 0.24 here: 0.23 ends the span mid-region)
         assert reuse_rows > 0
     model.close()
 
