@@ -288,10 +288,32 @@ def main():
         plain_ms = timed_steps(lambda tk, mk, pv: model.step(tk, mk, pv, fsp, out))
         refresh_ms = timed_steps(lambda tk, mk, pv: model.step_cached(tk, mk, pv, fsp, [b.CACHE_REFRESH] * B, None, out))
         reuse_ms = timed_steps(lambda tk, mk, pv: model.step_cached(tk, mk, pv, fsp, [b.CACHE_REUSE] * B, skip, out))
+        # with the prompt cached as well (prompt caching between refresh steps) only the span is recomputed
+        skip_all = skip.copy()
+        skip_all[:, :P] = 1
+        span_only_ms = timed_steps(lambda tk, mk, pv: model.step_cached(tk, mk, pv, fsp, [b.CACHE_REUSE] * B, skip_all, out))
+        # a slow-stage step that leaves the prompt out (rates the whole generated region)
+        pskip = np.zeros((B, L), np.uint8)
+        pskip[:, :P] = 1
+        slow_prompt_cached_ms = timed_steps(lambda tk, mk, pv: model.step_cached(tk, mk, pv, sps, [b.CACHE_REUSE] * B, pskip, out))
         result["fast_step_out_of_span_cache"] = {
             "span": span, "rows_total": B * L, "rows_recomputed_in_reuse_step": int(B * L - skip.sum()),
             "plain_fast_step_ms": plain_ms, "refresh_step_ms": refresh_ms, "reuse_step_ms": reuse_ms,
-            "note": "reuse steps recompute prompt + span only and read cached keys/values for the rest"}
+            "reuse_step_prompt_cached_ms": span_only_ms, "rows_recomputed_prompt_cached": int(B * L - skip_all.sum()),
+            "slow_step_prompt_cached_ms": slow_prompt_cached_ms, "slow_step_rows_recomputed": int(B * L - pskip.sum()),
+            "note": "reuse steps read cached keys/values for the positions they leave out; the first timed call of "
+                    "each variant follows a cache-filling call"}
+        # SlowFast decode with both caches on (thresholds as in decode_quantile_thresholds)
+        tokens, mask = tokens0.clone(), mask0.clone()
+        dpc = b.DecodeParams(10 ** 6, 8, 2, 1, 1, 0, 1.0, tau_min_q, tau_high_q, 1, 8)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        steps_c, st_c = model.decode(tokens, mask, P, dpc, stats_capacity=B * G)
+        t_c = time.perf_counter() - t0
+        result["decode_quantile_thresholds_cached"] = {
+            "generated_tokens_per_s": B * G / t_c, "steps": steps_c, "seconds": t_c,
+            "mean_step_ms": sum(x[4] for x in st_c) / max(len(st_c), 1),
+            "params": "as decode_quantile_thresholds, plus out_of_span_cache = 1 and prompt_cache_interval = 8"}
         result["cpu_baseline"] = cpu_baseline_step(mc, weights, tokens0)
         model.close()
         del model, weights

@@ -522,7 +522,7 @@ struct TileCfg {
 constexpr int kNumCfg = 6;
 const TileCfg kCfg[kNumCfg] = {
     {256, 256, 32, 4, 4, 1.85f, 9.0f}, {256, 192, 32, 5, 4, 1.40f, 8.0f}, {256, 128, 64, 3, 4, 0.88f, 6.0f},
-    {256, 96, 64, 3, 4, 0.77f, 5.0f},  {128, 128, 64, 4, 4, 0.62f, 3.5f}, {128, 64, 64, 4, 4, 0.40f, 2.5f},
+    {256, 96, 64, 3, 4, 0.77f, 5.0f},  {128, 128, 64, 4, 4, 0.62f, 3.5f}, {128, 64, 64, 4, 4, 1.00f, 2.5f},
 };
 constexpr int kNumCU = 256;
 
