@@ -19,17 +19,18 @@ __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// Round to nearest even; NaN stays NaN.
-__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
+// Round to nearest even; NaN stays NaN.  Written as a type conversion so that gfx950's
+// v_cvt_pk_bf16_f32 does it in one instruction per pair (the integer formulation costs ~10).
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_native;
+typedef __attribute__((ext_vector_type(2))) float floatx2_native;
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+    const floatx2_native v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_native));
+}
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+{
+    return (uint16_t)(pack_bf16x2(f, 0.0f) & 0xffffu);
 }
 
 __device__ __forceinline__ float wave_max(float v)
