@@ -118,6 +118,8 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__r
     const uint16_t *vbase = base + 2 * d + (size_t)h * DH;
     uint4 kreg[K_LOADS], vreg[V_BLOCKS][4];
 
+    const char *kbytes = reinterpret_cast<const char *>(kbase), *vbytes = reinterpret_cast<const char *>(vbase);
+    const uint32_t ldb = (uint32_t)ld * 2u;  // 32-bit byte offsets from the sequence base
     auto fetch = [&](int it) {  // step `it` of this half -> registers (zeros past the end)
         const int key0 = (my_first + it) * kKeys;
         const bool live = it < my_count;
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__r
         for (int t = 0; t < K_LOADS; ++t) {
             const int idx = htid + t * HT, row = idx / CH, ch = idx % CH;
             const int key = key0 + row;
-            kreg[t] = (live && key < L) ? *reinterpret_cast<const uint4 *>(kbase + (size_t)key * ld + ch * 8)
+            kreg[t] = (live && key < L) ? *reinterpret_cast<const uint4 *>(kbytes + ((uint32_t)key * ldb + (uint32_t)ch * 16u))
                                         : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__r
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int key = key0 + kg * 4 + r;
-                vreg[t][r] = (live && key < L && blk < V_TOTAL) ? *reinterpret_cast<const uint4 *>(vbase + (size_t)key * ld + dg * 8)
+                vreg[t][r] = (live && key < L && blk < V_TOTAL) ? *reinterpret_cast<const uint4 *>(vbytes + ((uint32_t)key * ldb + (uint32_t)dg * 16u))
                                                : make_uint4(0, 0, 0, 0);
             }
         }

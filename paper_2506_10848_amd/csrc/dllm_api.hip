@@ -862,6 +862,8 @@ int dllm_op_attention(void *hip_stream, const void *qkv, void *out, int32_t B, i
     if (!qkv || !out || !aligned16(qkv) || !aligned16(out)) return fail(nullptr, DLLM_EINVAL, "dllm_op_attention: null or misaligned pointer");
     if (B < 1 || L < 1 || H < 1 || (dh != 64 && dh != 128)) return fail(nullptr, DLLM_EINVAL, "dllm_op_attention: bad shape");
     if ((long)B > 65535 || (long)H > 65535) return fail(nullptr, DLLM_EINVAL, "dllm_op_attention: B and H must be <= 65535");
+    if ((double)L * 3.0 * H * dh * 2.0 >= 4.0e9)
+        return fail(nullptr, DLLM_EINVAL, "dllm_op_attention: one sequence of qkv must stay below 4 GB (32-bit offsets)");
     HIP_TRY(nullptr, launch_attention(static_cast<hipStream_t>(hip_stream), qkv, out, B, L, H, dh));
     return DLLM_OK;
 }
