@@ -145,7 +145,9 @@ __device__ __forceinline__ int w_global_row(int j, int n0, int N)
 // Accumulators hold the transposed 32x32 tiles: element e of lane l is output
 // row l % 32, tile column 8*(e/4) + 4*(l/32) + e%4.  n0 is the first output
 // column (plain) or the first pair (paired) of the workgroup's tile.
-template <int TM, int TN, int WTM, int EPI>
+// GUARD = false: the workgroup's tile lies inside the matrix and N % 4 == 0, so no store needs a
+// bounds check (straight-line stores with immediate offsets instead of a masked branch per store).
+template <int TM, int TN, int WTM, int EPI, bool GUARD>
 __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, int M, int N, int m0, int n0, int wm,
                                            int wn, int l32, int lhalf, int split, const RopeArgs &rope)
 {
@@ -164,11 +166,11 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const float g = acc[i][j][4 * q + e], u = acc[i][j][8 + 4 * q + e];
-                        y[e] = g / (1.0f + __expf(-g)) * u;
+                        y[e] = g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;  // 1 ulp reciprocal, far below the bf16 rounding
                     }
-                    if (row >= M || col >= n_out) continue;
+                    if (GUARD && (row >= M || col >= n_out)) continue;
                     uint16_t *p = C + (size_t)row * n_out + col;
-                    if (col + 3 < n_out && (n_out & 3) == 0) {
+                    if (!GUARD || (col + 3 < n_out && (n_out & 3) == 0)) {
                         uint2 w;
                         w.x = pack_bf16x2(y[0], y[1]);
                         w.y = pack_bf16x2(y[2], y[3]);
@@ -193,7 +195,7 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
                 for (int q = 0; q < 2; ++q) {
                     const int p = n0 + (wn * TN + j) * 16 + 8 * q + 4 * lhalf;  // first of the lane's 4 pairs
                     const int pp = p % HD, col = (p / HD) * (2 * HD) + pp;
-                    if (row >= M || p >= N / 2) continue;
+                    if (GUARD && (row >= M || p >= N / 2)) continue;
                     float a[4], b[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -230,9 +232,9 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int col = n0 + (wn * TN + j) * 32 + 8 * q + 4 * lhalf;
-                    if (row >= M || col >= N) continue;
+                    if (GUARD && (row >= M || col >= N)) continue;
                     uint16_t *p = C + (size_t)row * N + col;
-                    if (col + 3 < N && (N & 3) == 0) {
+                    if (!GUARD || (col + 3 < N && (N & 3) == 0)) {
                         uint2 w;
                         w.x = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
                         w.y = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
@@ -252,9 +254,9 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int col = n0 + (wn * TN + j) * 32 + 8 * q + 4 * lhalf;
-                    if (row >= M || col >= N) continue;
+                    if (GUARD && (row >= M || col >= N)) continue;
                     float *p = C + (size_t)row * N + col;
-                    if (col + 3 < N && (N & 3) == 0) {
+                    if (!GUARD || (col + 3 < N && (N & 3) == 0)) {
                         *reinterpret_cast<float4 *>(p) = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1],
                                                                      acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
                     } else {
@@ -406,7 +408,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
     }
 #undef DLLM_COPY
 #undef DLLM_READ
-    store_tile<TM, TN, WTM, EPI>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
+    const int n_lim = epi_paired(EPI) ? N / 2 : N;
+    if constexpr (kSkipEmpty) {  // (the 256x256 tile has no register to spare for a second epilogue)
+        if (m0 + BM <= M && n0 + BN_OUT <= n_lim && (n_lim & 3) == 0 && (N & 3) == 0) {
+            store_tile<TM, TN, WTM, EPI, false>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
+            return;
+        }
+    }
+    store_tile<TM, TN, WTM, EPI, true>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
 }
 
 // ---- fallback kernel: any K % 8 == 0 -------------------------------------------
@@ -507,7 +516,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
     }
-    store_tile<TM, TN, WTM, EPI>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
+    store_tile<TM, TN, WTM, EPI, true>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
 }
 
 // ---- host side ----------------------------------------------------------------
