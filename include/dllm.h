@@ -264,7 +264,7 @@ int dllm_op_linear(void *hip_stream, const void *A, const void *W, void *C, int3
 /* out[M][f] = silu(A Wg^T) * (A Wu^T) with W = [gate | up] rows, [2f][K]. */
 int dllm_op_linear_swiglu(void *hip_stream, const void *A, const void *W, void *out, int32_t M, int32_t f,
                           int32_t K);
-/* x (fp32 [M][d], in/out) += sum of n_partials fp32 [M][d] slabs (may be 0);
+/* x (fp32 [M][d], in/out) += sum of n_partials fp32 [M][d] slabs (0 to 8);
  * h (bf16 [M][d]) = RMSNorm(x) * gain. */
 int dllm_op_add_rmsnorm(void *hip_stream, float *x, const float *partials, int32_t n_partials,
                         const void *gain, void *h, int32_t M, int32_t d, float eps);

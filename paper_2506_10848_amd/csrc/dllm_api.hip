@@ -826,7 +826,8 @@ int dllm_op_add_rmsnorm(void *hip_stream, float *x, const float *partials, int32
                         void *hout, int32_t M, int32_t d, float eps)
 {
     if (!x || !gain || !hout || (n_partials > 0 && !partials)) return fail(nullptr, DLLM_EINVAL, "dllm_op_add_rmsnorm: null argument");
-    if (M < 1 || d < 4 || d % 4 || n_partials < 0) return fail(nullptr, DLLM_EINVAL, "dllm_op_add_rmsnorm: need M >= 1, d a positive multiple of 4, n_partials >= 0");
+    if (M < 1 || d < 4 || d % 4 || n_partials < 0 || n_partials > kMaxSplits)
+        return fail(nullptr, DLLM_EINVAL, "dllm_op_add_rmsnorm: need M >= 1, d a positive multiple of 4, 0 <= n_partials <= %d", kMaxSplits);
     if (!aligned16(x) || !aligned16(gain) || !aligned16(hout) || !aligned16(partials)) return fail(nullptr, DLLM_EINVAL, "dllm_op_add_rmsnorm: pointers must be 16-byte aligned");
     HIP_TRY(nullptr, launch_add_rmsnorm(static_cast<hipStream_t>(hip_stream), x, partials, n_partials, gain, hout, M, d, eps));
     return DLLM_OK;

@@ -47,10 +47,16 @@ __global__ __launch_bounds__(kThreads) void add_rmsnorm_kernel(float *__restrict
     float ss = 0.0f;
     for (int c = threadIdx.x; c < d / 4; c += kThreads) {
         float4 v = xr[c];
-        for (int s = 0; s < n_partials; ++s) {
-            const float4 p = reinterpret_cast<const float4 *>(partials + s * slab + (size_t)r * d)[c];
-            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
-        }
+        // all slab loads are issued before the first add (a loop of unknown length would take them one
+        // latency at a time); the order of the additions stays s = 0, 1, ...
+        constexpr int kMaxPartials = 8;
+        float4 p[kMaxPartials];
+#pragma unroll
+        for (int s = 0; s < kMaxPartials; ++s)
+            if (s < n_partials) p[s] = reinterpret_cast<const float4 *>(partials + s * slab + (size_t)r * d)[c];
+#pragma unroll
+        for (int s = 0; s < kMaxPartials; ++s)
+            if (s < n_partials) { v.x += p[s].x; v.y += p[s].y; v.z += p[s].z; v.w += p[s].w; }
         if (n_partials) xr[c] = v;
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }

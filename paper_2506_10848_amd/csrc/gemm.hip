@@ -528,12 +528,17 @@ struct TileCfg {
     int bm, bn, bk, nst, waves;
     float step_us, epi_us;
 };
-constexpr int kNumCfg = 6;
+constexpr int kNumCfg = 7;
 const TileCfg kCfg[kNumCfg] = {
     {256, 256, 32, 4, 4, 1.85f, 9.0f}, {256, 192, 32, 5, 4, 1.40f, 8.0f}, {256, 128, 64, 3, 4, 0.88f, 6.0f},
     {256, 96, 64, 3, 4, 0.77f, 5.0f},  {128, 128, 64, 4, 4, 0.62f, 3.5f}, {128, 64, 64, 4, 4, 1.00f, 2.5f},
+    {64, 64, 64, 8, 4, 0.30f, 1.5f},  // few rows (cached steps): a deep ring keeps 56 KB of weights in flight per workgroup
 };
 constexpr int kNumCU = 256;
+constexpr int kLdsPerCU = 160 * 1024;
+// Weight streaming: a workgroup keeps (NST - 1) stages of its W tile in flight and a request takes about
+// 2 us under load, so few or shallow workgroups cannot pull the ~5 TB/s the HBM delivers to this pattern.
+constexpr double kHbmBytesPerUs = 5.0e6, kLoadLatencyUs = 2.0;
 
 struct Plan {
     int cfg, splits;
@@ -583,7 +588,17 @@ Plan make_plan(int epi, int M, int N, int K)
             const long rounds = (wgs + kNumCU - 1) / kNumCU;
             // a round that leaves CUs idle runs its workgroups faster (power and bandwidth are shared by fewer)
             const double fill = (double)wgs / (double)(rounds * kNumCU);
-            double cost = (double)rounds * ((double)(kps / 64) * t.step_us * (0.55 + 0.45 * fill) + t.epi_us + 1.5);
+            // sub-tiles without rows are skipped by the kernel
+            const int m_tiles = (M + t.bm - 1) / t.bm;
+            const double rows_frac = (double)((M + 31) / 32 * 32) / (double)(m_tiles * t.bm);
+            const double compute = (double)rounds * (double)(kps / 64) * t.step_us * (0.55 + 0.45 * fill) * rows_frac;
+            const int per_cu = kLdsPerCU / (t.nst * (t.bm + t.bn) * t.bk * 2) >= 2 ? 2 : 1;
+            const double in_flight = (double)(wgs < (long)kNumCU * per_cu ? wgs : (long)kNumCU * per_cu) *
+                                     (double)((t.nst - 1) * t.bn * t.bk * 2);
+            const double bw = in_flight / kLoadLatencyUs < kHbmBytesPerUs ? in_flight / kLoadLatencyUs : kHbmBytesPerUs;
+            const long cap = (long)kNumCU * per_cu;  // a partly filled last round streams at a lower rate
+            const double stream = (double)N * K * 2.0 / bw * (wgs > cap ? (double)((wgs + cap - 1) / cap * cap) / (double)wgs : 1.0);
+            double cost = (compute > stream ? compute : stream) + (double)rounds * (t.epi_us + 1.5);
             if (epi == kEpiPartial) cost += (double)s * M * N * 8.0 / 4.0e6;  // slab write + read, ~4 TB/s
             if (cost < best_cost) { best_cost = cost; best = Plan{c, s, fast}; }
         }
@@ -643,7 +658,8 @@ hipError_t dispatch(hipStream_t stream, Plan p, const void *A, const void *W, vo
     case 2: return launch_cfg<256, 128, 2, 2, 64, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
     case 3: return launch_cfg<256, 96, 4, 1, 64, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
     case 4: return launch_cfg<128, 128, 2, 2, 64, 4, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
-    default: return launch_cfg<128, 64, 2, 2, 64, 4, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
+    case 5: return launch_cfg<128, 64, 2, 2, 64, 4, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
+    default: return launch_cfg<64, 64, 2, 2, 64, 8, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
     }
 }
 
