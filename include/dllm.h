@@ -170,6 +170,16 @@ const char *dllm_last_error(const dllm_handle *h);
 int dllm_step(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *mask, int32_t *prev_pred,
               const dllm_stage_params *sp, const dllm_commit_list *out);
 
+/* Where the greedy decode and the confidence (Section 3.1, eq. 3 and the confidence it defines)
+ * of dllm_step / dllm_step_cached / the decode calls are computed.  enable != 0 (the default):
+ * inside the vocabulary projection, on its accumulators after the rounding to bf16; the logits
+ * are never written, each wave leaves (max, sum of exp, argmax) of its column slice per row and a
+ * merge kernel combines the slices.  enable == 0: the projection writes bf16 logits
+ * (dllm_debug_logits can read them) and a separate kernel reads them back.  Both take argmax and
+ * maximum over the same bf16 values, so predictions are identical; the confidences differ by the
+ * order of an fp32 sum.  Takes effect from the next step. */
+int dllm_set_fused_selector(dllm_handle *h, int32_t enable);
+
 /* dllm_step with out-of-span caching (Section 3.3, "Out-of-Span Caching"; Algorithm 1, fast
  * phase: "cache features for position i").  The features kept per position are its keys (after
  * the rotary embedding) and values in every layer.  Per sequence, cache_mode is
@@ -227,7 +237,8 @@ int dllm_decode_low_confidence(dllm_handle *h, int32_t B, int32_t L, int32_t gen
 /* Test and measurement hooks: device pointers into the workspace, valid until
  * the next call on the handle.  logits: bf16 [B*L][vocab] of the last forward
  * (after dllm_step only the rows inside each sequence's window are defined:
- * the vocabulary projection skips rows the selector does not read);
+ * the vocabulary projection skips rows the selector does not read; and none
+ * are written by a step while the fused selector is on);
  * pred / conf: int32 / float [B*L] of the last row phase (defined at the
  * masked positions of each window only). */
 int dllm_debug_logits(dllm_handle *h, const void **logits);

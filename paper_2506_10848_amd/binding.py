@@ -62,7 +62,7 @@ class StepStat(C.Structure):
                 ("ms", C.c_float)]
 
 
-EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_step_cached", "dllm_decode", "dllm_decode_low_confidence", "dllm_debug_logits",
+EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_step_cached", "dllm_decode", "dllm_decode_low_confidence", "dllm_set_fused_selector", "dllm_debug_logits",
            "dllm_debug_rows", "dllm_profile_begin", "dllm_profile_end", "dllm_forward", "dllm_select", "dllm_op_linear", "dllm_op_linear_swiglu",
            "dllm_op_add_rmsnorm", "dllm_op_rope", "dllm_op_linear_qkv_rope", "dllm_op_attention"]
 
@@ -206,6 +206,10 @@ class Model:
         cl = out.c_struct()
         _check(lib().dllm_step(self._h, B, L, _ptr(tokens), _ptr(mask), _ptr(prev_pred), _sp_array(sps),
                                C.byref(cl)), self._h)
+
+    def set_fused_selector(self, enable: bool) -> None:
+        """dllm_set_fused_selector: greedy decode inside the vocabulary projection (default) or from bf16 logits."""
+        _check(lib().dllm_set_fused_selector(self._h, int(bool(enable))), self._h)
 
     def step_cached(self, tokens, mask, prev_pred, sps, cache_mode, skip, out: "CommitList") -> None:
         """dllm_step_cached: cache_mode is a sequence of B ints, skip a host uint8 array [B, L] or None."""

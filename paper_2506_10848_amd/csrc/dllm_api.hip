@@ -24,6 +24,7 @@ struct Workspace {
     uint16_t *act = nullptr;     // [M][f]
     float *partials = nullptr;   // split-K slabs fp32 [kMaxSplits][M][d]
     uint16_t *logits = nullptr;  // [M][V]
+    float *rowstats = nullptr;   // [3][gemm_rowstats_max_parts(V)][M]: per-slice (max, sum of exp, argmax) of the fused selector
     int32_t *pred = nullptr;     // [M]
     float *conf = nullptr;       // [M]
     float2 *rope = nullptr;      // [max_seq][dh/2]
@@ -53,6 +54,7 @@ struct dllm_handle {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     std::string err;
     int last_B = 0, last_L = 0;
+    bool fused_selector = true;  // dllm_set_fused_selector
     // measurement hook: event pairs around the gate/up GEMM launches
     std::vector<hipEvent_t> prof_ev;
     int prof_cap = 0, prof_used = 0;
@@ -146,9 +148,30 @@ int check_commit_list(dllm_handle *h, const dllm_commit_list *o, CommitOut *c)
     return DLLM_OK;
 }
 
+// Vocabulary projection over n consecutive rows of the normalised hidden states, starting at row
+// h_row of ws.h; abs_row is the batch row (b * L + i) of the first of them.  With the fused selector
+// and a mask, the projection leaves per-slice row statistics instead of logits and the merge
+// kernel turns them into ws.pred / ws.conf at the masked rows of the windows.
+int vocab_rows(dllm_handle *h, long h_row, long abs_row, int n, int L, const uint8_t *mask, const SelectArgs *win)
+{
+    const dllm_config &c = h->cfg;
+    Workspace &w = h->ws;
+    if (h->fused_selector && mask && win) {
+        int parts = 0;
+        HIP_TRY(h, launch_gemm_rowstats(h->stream, w.h + h_row * c.d_model, h->lm_head, w.rowstats, n, c.vocab, c.d_model,
+                                        c.mask_id, &parts));
+        HIP_TRY(h, launch_rowstats_merge(h->stream, w.rowstats, parts, n, (int)abs_row, L, mask, *win, w.pred, w.conf));
+    } else {
+        HIP_TRY(h, launch_gemm(h->stream, kEpiBf16, w.h + h_row * c.d_model, h->lm_head, w.logits + abs_row * (long)c.vocab,
+                               n, c.vocab, c.d_model));
+    }
+    return DLLM_OK;
+}
+
 // `win` (nullable): per-sequence windows; the vocabulary projection then only
 // covers the rows lo..hi of each sequence (the rows the selector reads).
-int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const SelectArgs *win)
+// `mask` (nullable): see vocab_rows.
+int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const SelectArgs *win, const uint8_t *mask = nullptr)
 {
     const dllm_config &c = h->cfg;
     const int M = B * L, d = c.d_model, f = c.d_ffn;
@@ -190,8 +213,7 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const Sele
                 last = (long)e * L + win->w[e].hi;
                 ++e;
             }
-            HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h + first * d, h->lm_head, w.logits + first * (long)c.vocab,
-                                   (int)(last - first + 1), c.vocab, d));
+            if (int rc = vocab_rows(h, first, first, (int)(last - first + 1), L, mask, win)) return rc;
             b = e;
         }
     }
@@ -204,7 +226,8 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const Sele
 // not recomputed; every other position is recomputed from the current tokens, attends to all L positions
 // of its sequence (cached keys/values for the skipped ones) and refreshes its own cache rows.  The
 // vocabulary projection covers rows lo..eval_hi of each window; none of them may be skipped.
-int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const SelectArgs &win, const uint8_t *skip)
+int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const SelectArgs &win, const uint8_t *skip,
+                        const uint8_t *mask)
 {
     const dllm_config &c = h->cfg;
     const int d = c.d_model, f = c.d_ffn;
@@ -274,8 +297,7 @@ int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, con
         for (int i = 0; i < sw.lo; ++i) first_cmp += !(skip && skip[(size_t)b * L + i]);
         for (int i = sw.lo; i <= sw.eval_hi; ++i)
             if (skip && skip[(size_t)b * L + i]) return fail(h, DLLM_EINVAL, "sequence %d: position %d is skipped but inside the window", b, i);
-        HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h + first_cmp * d, h->lm_head, w.logits + first_abs * (long)c.vocab,
-                               (int)n, c.vocab, d));
+        if (int rc = vocab_rows(h, first_cmp, first_abs, (int)n, L, mask, &win)) return rc;
     }
     if (!any_skip) { w.cache_valid = true; w.cache_B = B; w.cache_L = L; }
     h->last_B = B;
@@ -443,6 +465,7 @@ int dllm_create(const dllm_config *cfg, const dllm_weights *w, void *hip_stream,
     A(dev_alloc(h, &s.act, M * f));
     A(dev_alloc(h, &s.partials, (size_t)kMaxSplits * M * d));
     A(dev_alloc(h, &s.logits, M * (size_t)c.vocab));
+    A(dev_alloc(h, &s.rowstats, 3 * gemm_rowstats_max_parts(c.vocab) * M));
     A(dev_alloc(h, &s.pred, M));
     A(dev_alloc(h, &s.conf, M));
     A(dev_alloc(h, &s.rope, (size_t)c.max_seq * (c.head_dim / 2)));
@@ -501,10 +524,18 @@ int dllm_step(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *ma
     if ((rc = check_commit_list(h, out, &co))) return rc;
     SelectArgs args;
     if ((rc = build_select_args(h, B, L, sp, out->capacity, &args))) return rc;
-    if ((rc = forward_impl(h, B, L, tokens, &args))) return rc;
-    HIP_TRY(h, launch_row_phase(h->stream, h->ws.logits, B, L, h->cfg.vocab, h->cfg.mask_id, mask, args, h->ws.pred,
-                                h->ws.conf));
+    if ((rc = forward_impl(h, B, L, tokens, &args, mask))) return rc;
+    if (!h->fused_selector)
+        HIP_TRY(h, launch_row_phase(h->stream, h->ws.logits, B, L, h->cfg.vocab, h->cfg.mask_id, mask, args, h->ws.pred,
+                                    h->ws.conf));
     HIP_TRY(h, launch_seq_phase(h->stream, B, L, tokens, mask, prev_pred, h->ws.pred, h->ws.conf, args, co));
+    return DLLM_OK;
+}
+
+int dllm_set_fused_selector(dllm_handle *h, int32_t enable)
+{
+    if (!h) return fail(nullptr, DLLM_EINVAL, "dllm_set_fused_selector: null handle");
+    h->fused_selector = enable != 0;
     return DLLM_OK;
 }
 
@@ -526,7 +557,7 @@ int dllm_step_cached(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint
     }
     if (any_reuse && !skip) return fail(h, DLLM_EINVAL, "dllm_step_cached: a sequence reuses the cache but skip is null");
     if (!any_cache) {
-        if ((rc = forward_impl(h, B, L, tokens, &args))) return rc;
+        if ((rc = forward_impl(h, B, L, tokens, &args, mask))) return rc;
     } else {
         // only sequences in reuse mode skip anything
         std::vector<uint8_t> eff;
@@ -542,10 +573,11 @@ int dllm_step_cached(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint
                 }
             }
         }
-        if ((rc = forward_cached_impl(h, B, L, tokens, args, any_reuse ? eff.data() : nullptr))) return rc;
+        if ((rc = forward_cached_impl(h, B, L, tokens, args, any_reuse ? eff.data() : nullptr, mask))) return rc;
     }
-    HIP_TRY(h, launch_row_phase(h->stream, h->ws.logits, B, L, h->cfg.vocab, h->cfg.mask_id, mask, args, h->ws.pred,
-                                h->ws.conf));
+    if (!h->fused_selector)
+        HIP_TRY(h, launch_row_phase(h->stream, h->ws.logits, B, L, h->cfg.vocab, h->cfg.mask_id, mask, args, h->ws.pred,
+                                    h->ws.conf));
     HIP_TRY(h, launch_seq_phase(h->stream, B, L, tokens, mask, prev_pred, h->ws.pred, h->ws.conf, args, co));
     return DLLM_OK;
 }

@@ -115,12 +115,19 @@ __device__ __forceinline__ void tile_of(int pid, int num_m, int num_n, int &pid_
 // Rotary embedding fused into the QKV projection's epilogue: output columns
 // below rope_cols (the q and k thirds) are rotated in fp32 before the bf16
 // rounding; pos = row % L, table[pos][j] = (cos, sin) of pos * theta^(-2j/dh).
+//
+// The row-statistics epilogue (greedy decode and confidence of Section 3.1 eq. 3 taken on the
+// accumulators of the vocabulary projection, so that the logits are never written) reuses the two
+// integers: `parts` column slices per row (one per wave column of every tile) and the id of the
+// [MASK] token, which is not a legal prediction.
 struct RopeArgs {
     const float2 *table;
     const int32_t *pos;  // nullable: position of every row (rows of a gathered subset)
-    int L, rope_cols;
+    union { int L; int parts; };
+    union { int rope_cols; int mask_id; };
 };
 constexpr int kEpiRope64 = 3, kEpiRope128 = 4;  // head_dim is a compile-time constant of the epilogue
+constexpr int kEpiRowStats = 5;
 
 __host__ __device__ constexpr bool epi_paired(int epi) { return epi == kEpiSwiglu || epi == kEpiRope64 || epi == kEpiRope128; }
 __host__ __device__ constexpr int epi_head_dim(int epi) { return epi == kEpiRope128 ? 128 : 64; }
@@ -151,7 +158,58 @@ template <int TM, int TN, int WTM, int EPI, bool GUARD>
 __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, int M, int N, int m0, int n0, int wm,
                                            int wn, int l32, int lhalf, int split, const RopeArgs &rope)
 {
-    if (EPI == kEpiSwiglu) {
+    if constexpr (EPI == kEpiRowStats) {
+        // Cout: fp32 max [parts][M], fp32 sum of exp(x - max) [parts][M], int32 lowest column of the max
+        // [parts][M]; x = the logit rounded to bf16 (what the unfused path stores and reads back); the
+        // slice of this wave is part n0 / (32 TN) + wn.  A slice without a legal column leaves (-3e38, 0).
+        constexpr float kLog2e = 1.4426950408889634f, kNegBig = -3.0e38f;
+        const size_t plane = (size_t)rope.parts * M;
+        float *pm = reinterpret_cast<float *>(Cout) + (size_t)(n0 / (32 * TN) + wn) * M;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = m0 + wm * WTM + i * 32 + l32;
+            float m = kNegBig;
+            int c = 0x7fffffff;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = n0 + (wn * TN + j) * 32 + 8 * q + 4 * lhalf;
+                    const uint32_t w01 = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+                    const uint32_t w23 = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                    const float x[4] = {__uint_as_float(w01 << 16), __uint_as_float(w01 & 0xffff0000u),
+                                        __uint_as_float(w23 << 16), __uint_as_float(w23 & 0xffff0000u)};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const bool legal = col + e < N && col + e != rope.mask_id;
+                        const float v = legal ? x[e] : -INFINITY;
+                        acc[i][j][4 * q + e] = v;
+                        if (v > m) {  // columns are visited in increasing order: the first maximum stays
+                            m = v;
+                            c = col + e;
+                        }
+                    }
+                }
+            const float off = -m * kLog2e;
+            float s = 0.0f;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) s += __builtin_amdgcn_exp2f(fmaf(acc[i][j][e], kLog2e, off));
+            s = m > kNegBig ? s : 0.0f;
+            // the other half of the row's columns sits in lane ^ 32
+            const float m2 = __shfl_xor(m, 32, 64), s2 = __shfl_xor(s, 32, 64);
+            const int c2 = __shfl_xor(c, 32, 64);
+            const float mt = fmaxf(m, m2);
+            const float st = s * __builtin_amdgcn_exp2f((m - mt) * kLog2e) + s2 * __builtin_amdgcn_exp2f((m2 - mt) * kLog2e);
+            const int ct = (m > m2 || (m == m2 && c < c2)) ? c : c2;
+            if (lhalf == 0 && row < M) {
+                pm[row] = mt;
+                pm[plane + row] = st;
+                reinterpret_cast<int *>(pm)[2 * plane + row] = ct;
+            }
+        }
+    } else if (EPI == kEpiSwiglu) {
         uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
         const int n_out = N / 2;
 #pragma unroll
@@ -525,14 +583,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *
 // microseconds when every CU holds a workgroup (measured on MI355X at M = 512 with
 // random operands; under that load the shader clock sits near 1.5 GHz).
 struct TileCfg {
-    int bm, bn, bk, nst, waves;
+    int bm, bn, bk, nst, wn;  // wn: wave columns of the tile
     float step_us, epi_us;
 };
 constexpr int kNumCfg = 7;
 const TileCfg kCfg[kNumCfg] = {
-    {256, 256, 32, 4, 4, 1.85f, 9.0f}, {256, 192, 32, 5, 4, 1.40f, 8.0f}, {256, 128, 64, 3, 4, 0.88f, 6.0f},
-    {256, 96, 64, 3, 4, 0.77f, 5.0f},  {128, 128, 64, 4, 4, 0.62f, 3.5f}, {128, 64, 64, 4, 4, 1.00f, 2.5f},
-    {64, 64, 64, 8, 4, 0.30f, 1.5f},  // few rows (cached steps): a deep ring keeps 56 KB of weights in flight per workgroup
+    {256, 256, 32, 4, 2, 1.85f, 9.0f}, {256, 192, 32, 5, 2, 1.40f, 8.0f}, {256, 128, 64, 3, 2, 0.88f, 6.0f},
+    {256, 96, 64, 3, 1, 0.77f, 5.0f},  {128, 128, 64, 4, 2, 0.62f, 3.5f}, {128, 64, 64, 4, 2, 1.00f, 2.5f},
+    {64, 64, 64, 8, 2, 0.30f, 1.5f},  // few rows (cached steps): a deep ring keeps 56 KB of weights in flight per workgroup
 };
 constexpr int kNumCU = 256;
 constexpr int kLdsPerCU = 160 * 1024;
@@ -556,7 +614,9 @@ bool cfg_allows(int c, int epi, bool fast)
 {
     if (!fast && c < 2) return false;  // the register-staged kernel keeps to the smaller tiles
     // 256 accumulator registers per lane leave no room for the fp32 and the rotary epilogue
-    if (c == 0 && (epi == kEpiPartial || epi == kEpiRope64 || epi == kEpiRope128)) return false;
+    if (c == 0 && (epi == kEpiPartial || epi == kEpiRope64 || epi == kEpiRope128 || epi == kEpiRowStats)) return false;
+    // a wave's slice of a row is at least 64 columns wide, which bounds the partial results per row
+    if (epi == kEpiRowStats && kCfg[c].bn / kCfg[c].wn < 64) return false;
     return true;
 }
 
@@ -608,7 +668,7 @@ Plan make_plan(int epi, int M, int N, int K)
 
 template <int BM, int BN, int WM, int WN, int BK, int NST, int EPI>
 hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *W, void *C, int M, int N, int K,
-                      int splits, RopeArgs rope = RopeArgs{nullptr, nullptr, 1, 0})
+                      int splits, RopeArgs rope = RopeArgs{nullptr, nullptr, {1}, {0}})
 {
     constexpr int BN_OUT = epi_paired(EPI) ? BN / 2 : BN;
     const int n_lim = epi_paired(EPI) ? N / 2 : N;
@@ -647,7 +707,7 @@ hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *
 
 template <int EPI>
 hipError_t dispatch(hipStream_t stream, Plan p, const void *A, const void *W, void *C, int M, int N, int K,
-                    RopeArgs rope = RopeArgs{nullptr, nullptr, 1, 0})
+                    RopeArgs rope = RopeArgs{nullptr, nullptr, {1}, {0}})
 {
     switch (p.cfg) {
     case 0:
@@ -677,10 +737,25 @@ bool gemm_qkv_rope_supported(int M, int d, int dh)
 hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
                                 const float2 *table, int L, const int32_t *pos)
 {
-    const RopeArgs rope{table, pos, L, 2 * d};
+    const RopeArgs rope{table, pos, {L}, {2 * d}};
     const Plan p = make_plan(dh == 128 ? kEpiRope128 : kEpiRope64, M, 3 * d, d);
     if (dh == 128) return dispatch<kEpiRope128>(stream, p, A, W, C, M, 3 * d, d, rope);
     return dispatch<kEpiRope64>(stream, p, A, W, C, M, 3 * d, d, rope);
+}
+
+size_t gemm_rowstats_max_parts(int N) { return (size_t)(N + 63) / 64 + 1; }
+
+hipError_t launch_gemm_rowstats(hipStream_t stream, const void *A, const void *W, float *stats, int M, int N, int K,
+                                int mask_id, int *parts)
+{
+    const Plan p = make_plan(kEpiRowStats, M, N, K);
+    const TileCfg &t = kCfg[p.cfg];
+    *parts = (N + t.bn - 1) / t.bn * t.wn;
+    if ((size_t)*parts > gemm_rowstats_max_parts(N)) return hipErrorInvalidValue;
+    RopeArgs ea{nullptr, nullptr, {0}, {0}};
+    ea.parts = *parts;
+    ea.mask_id = mask_id;
+    return dispatch<kEpiRowStats>(stream, p, A, W, stats, M, N, K, ea);
 }
 
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,

@@ -32,6 +32,9 @@ hipError_t launch_row_phase(hipStream_t stream, const void *logits, int B, int L
                             const uint8_t *mask, const SelectArgs &args, int32_t *pred, float *conf);
 hipError_t launch_seq_phase(hipStream_t stream, int B, int L, int32_t *tokens, uint8_t *mask, int32_t *prev_pred,
                             const int32_t *pred, const float *conf, const SelectArgs &args, const CommitOut &out);
+// Row phase from the statistics that launch_gemm_rowstats left for rows first_row .. first_row + n_rows - 1.
+hipError_t launch_rowstats_merge(hipStream_t stream, const float *stats, int parts, int n_rows, int first_row, int L,
+                                 const uint8_t *mask, const SelectArgs &args, int32_t *pred, float *conf);
 
 // ---- forward pass -------------------------------------------------------------
 // rows (nullable): x[r] is the embedding of tokens[rows[r]] instead of tokens[r]
@@ -69,5 +72,12 @@ hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W
 // C = A[M][K] * W[N][K]^T.  For kEpiSwiglu N counts gate + up rows.
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
                        int K);
+// The same product with the greedy decode fused in: no C; per row and per column slice (a wave's
+// share of a tile, *parts of them) the maximum of the bf16-rounded values, the sum of
+// exp(x - max) and the lowest column holding the maximum, column mask_id left out.
+// stats: fp32/int32 planes [3][*parts][M]; *parts <= gemm_rowstats_max_parts(N).
+size_t gemm_rowstats_max_parts(int N);
+hipError_t launch_gemm_rowstats(hipStream_t stream, const void *A, const void *W, float *stats, int M, int N, int K,
+                                int mask_id, int *parts);
 
 }  // namespace dllm

@@ -166,6 +166,33 @@ __global__ __launch_bounds__(kRowThreads) void row_phase_kernel(const uint16_t *
     }
 }
 
+// Row phase after a vocabulary projection with the row-statistics epilogue: the statistics of
+// `parts` column slices per row, planes of [parts][n_rows] (max, sum of exp(x - max), lowest
+// column holding the max), are merged with the same log-sum-exp rule.  Row lr of the planes is
+// batch row first_row + lr.
+__global__ __launch_bounds__(kRowThreads) void rowstats_merge_kernel(const float *__restrict__ stats, int parts,
+                                                                     int n_rows, int first_row, int L,
+                                                                     const uint8_t *__restrict__ mask, SelectArgs args,
+                                                                     int32_t *__restrict__ pred, float *__restrict__ conf)
+{
+    const int lr = blockIdx.x, r = first_row + lr;
+    const int b = r / L, i = r - b * L;
+    const SeqWindow w = args.w[b];
+    if (i < w.lo || i > w.eval_hi || mask[r] == 0) return;  // uniform over the block
+    const size_t plane = (size_t)parts * n_rows;
+    const int *cols = reinterpret_cast<const int *>(stats) + 2 * plane;
+    RowAcc acc{kNegBig, 0.0f, 0x7fffffff};
+    for (int p = threadIdx.x; p < parts; p += kRowThreads) {
+        const size_t at = (size_t)p * n_rows + lr;
+        acc = combine(acc, RowAcc{stats[at], stats[plane + at], cols[at]});
+    }
+    const RowAcc tot = block_reduce(acc);
+    if (threadIdx.x == 0) {
+        pred[r] = tot.c;
+        conf[r] = 1.0f / tot.s;
+    }
+}
+
 // ---- sequence phase ---------------------------------------------------------
 
 constexpr int kSeqThreads = 512;
@@ -298,6 +325,14 @@ hipError_t launch_row_phase(hipStream_t stream, const void *logits, int B, int L
     else
         hipLaunchKernelGGL(row_phase_kernel<false>, grid, block, 0, stream, (const uint16_t *)logits, L, V, mask_id,
                            mask, args, pred, conf);
+    return hipGetLastError();
+}
+
+hipError_t launch_rowstats_merge(hipStream_t stream, const float *stats, int parts, int n_rows, int first_row, int L,
+                                 const uint8_t *mask, const SelectArgs &args, int32_t *pred, float *conf)
+{
+    hipLaunchKernelGGL(rowstats_merge_kernel, dim3(n_rows), dim3(kRowThreads), 0, stream, stats, parts, n_rows,
+                       first_row, L, mask, args, pred, conf);
     return hipGetLastError();
 }
 

@@ -302,6 +302,7 @@ def run_cached_forward(cfg, batch, span, std=0.02, sample=None):
     P = cfg["prompt"]
     s, e = P, P + span - 1
     model = b.Model(mc, wd, B, L)
+    model.set_fused_selector(False)              # the steps below must leave logits to compare
     out = b.CommitList(B, L)
     sps = [b.stage_params(b.STAGE_FAST, s, e, 1, 0.1, 0.9, 0, P, L) for _ in range(B)]
     g_tok, g_mask, g_prev = tokens.to(DEV), mask.to(DEV), prev.to(DEV)

@@ -191,7 +191,12 @@ class CachedSpanDriver:
         return self._skip
 
 
-def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9, driver=None):
+FUSED = pytest.mark.parametrize("fused", [False, True], ids=["logits", "fused"])
+
+
+def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9, driver=None, fused=False):
+    """fused: the greedy decode runs inside the vocabulary projection and leaves no logits, so the
+    logits comparison is the unfused run's; every decision is checked the same way in both."""
     b = binding()
     w = synth.make_weights(cfg)
     if final_gain != 1.0:
@@ -203,6 +208,7 @@ def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9, driv
     B, L = tokens.shape
     P = cfg["prompt"]
     model = b.Model(mc, wd, B, L)
+    model.set_fused_selector(fused)
     out = b.CommitList(B, L)
     stats = dict(steps=0, exact=0, loose=0, tokens_checked=0, max_logit_err=0.0)
 
@@ -236,7 +242,7 @@ def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9, driv
         else:
             model.step(g_tok, g_mask, g_prev, csp, out)
         torch.cuda.synchronize()
-        g_logits = oracle.bf16_to_f64(bits(model.debug_logits(B * L)))
+        g_logits = None if fused else oracle.bf16_to_f64(bits(model.debug_logits(B * L)))
         got = out.to_host()
         mask_before, prev_before, tok_before = mask.copy(), prev_pred.copy(), tokens.copy()
         res = sf.step(predict, tokens, mask, prev_pred, sps, skip, also)
@@ -249,9 +255,10 @@ def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9, driv
         wrows = [s * L + i for s in range(B) for i in range(sps[s].eval_window()[0], sps[s].eval_window()[1] + 1)]
         assert not np.isnan(ref[wrows]).any()
         top = np.nanmax(np.abs(ref))
-        err = np.abs(g_logits[wrows] - ref[wrows]).max() / top
-        stats["max_logit_err"] = max(stats["max_logit_err"], err)
-        assert err <= 2e-2 and err <= LOGIT_NORMWISE
+        if not fused:
+            err = np.abs(g_logits[wrows] - ref[wrows]).max() / top
+            stats["max_logit_err"] = max(stats["max_logit_err"], err)
+            assert err <= 2e-2 and err <= LOGIT_NORMWISE
         eps_abs = LOGIT_NORMWISE * top
         delta = math.exp(2 * eps_abs) - 1
         srt = np.sort(np.where(np.arange(ref.shape[1]) == mc["mask_id"], -np.inf, np.nan_to_num(ref)), axis=1)
@@ -303,35 +310,39 @@ def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9, driv
     return stats
 
 
-def test_lockstep_tiny_config_full_decode():
+@FUSED
+def test_lockstep_tiny_config_full_decode(fused):
     """Random-init tiny config, the paper's default hyper-parameters (threshold
     0.9): confidences are ~1/V everywhere, so only top-k / empty-e_cand paths run."""
     cfg = synth.CONFIGS["tiny"]
     p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.1, tau_high_conf=0.9, conv_mode=1)
-    st = lockstep(cfg, cfg["batch"], p)
+    st = lockstep(cfg, cfg["batch"], p, fused=fused)
     assert st["steps"] == cfg["gen"]                # one token per step under random init
     print("lockstep tiny:", st)
 
 
-def test_lockstep_tiny_config_peaked_logits():
+@FUSED
+def test_lockstep_tiny_config_peaked_logits(fused):
     """Same model with the final norm gain raised so that confidences spread
     over (0, 1): threshold, convergence-gate and e_cand paths run end to end."""
     cfg = synth.CONFIGS["tiny"]
     p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.2, tau_high_conf=0.3, conv_mode=1, k_slow=2)
-    st = lockstep(cfg, 2, p, final_gain=10.0)
+    st = lockstep(cfg, 2, p, final_gain=10.0, fused=fused)
     assert st["steps"] < cfg["gen"]                 # parallel commits happened
     assert st["exact"] >= st["loose"]
     print("lockstep tiny peaked:", st)
 
 
-def test_lockstep_medium_config_first_steps():
+@FUSED
+def test_lockstep_medium_config_first_steps(fused):
     cfg = synth.CONFIGS["medium"]
     p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.1, tau_high_conf=0.9, conv_mode=1)
-    st = lockstep(cfg, 2, p, max_checked_steps=3)
+    st = lockstep(cfg, 2, p, max_checked_steps=3, fused=fused)
     print("lockstep medium:", st)
 
 
-def test_lockstep_out_of_span_caching():
+@FUSED
+def test_lockstep_out_of_span_caching(fused):
     """SlowFast with out-of-span caching (Section 3.3): refresh and reuse steps of both sides start
     from the oracle's state and the oracle's cached set; the library's stale-feature forward must
     stay inside the same logit bound, and the decisions are compared as in the other lock-step runs."""
@@ -345,41 +356,44 @@ def test_lockstep_out_of_span_caching():
     _, c0 = OraclePredictor(synth.model_config(cfg), weights_bits(w), B, L)(tokens, mask)
     tau_min = float(np.median(c0[mask == 1]))
     st = lockstep(cfg, 2, None, final_gain=10.0, max_checked_steps=40,
-                  driver=lambda B, P, L: CachedSpanDriver(B, P, L, 8, tau_min))
+                  driver=lambda B, P, L: CachedSpanDriver(B, P, L, 8, tau_min), fused=fused)
     assert st["cached_steps"] == 40 and st["rows_skipped"] > 200
     print("lockstep cached:", st)
 
 
-def test_lockstep_out_of_span_caching_random_init():
+@FUSED
+def test_lockstep_out_of_span_caching_random_init(fused):
     # confidences ~ 1/V < tau_min everywhere: every masked position right of the span is cached
     cfg = synth.CONFIGS["tiny"]
     # (spans are single positions here, so every fast stage is one refresh step: covers the wide
     # evaluation window of a refresh step and mixed slow / refresh batches under Algorithm 1's controller)
     p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.1, tau_high_conf=0.9, conv_mode=0, k_fast=1, k_max=2,
                         out_of_span_cache=True)
-    st = lockstep(cfg, 2, p, max_checked_steps=24)
+    st = lockstep(cfg, 2, p, max_checked_steps=24, fused=fused)
     assert st.get("cached_steps", 0) >= 4
     print("lockstep cached, random init:", st)
 
 
-def test_lockstep_prompt_caching():
+@FUSED
+def test_lockstep_prompt_caching(fused):
     """Prompt caching (K_p = 4) together with out-of-span caching under Algorithm 1's controller:
     three of four steps recompute the generated region only."""
     cfg = synth.CONFIGS["tiny"]
     p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.2, tau_high_conf=0.3, conv_mode=1, k_slow=2,
                         out_of_span_cache=True, prompt_cache_interval=4)
-    st = lockstep(cfg, 2, p, final_gain=10.0)
+    st = lockstep(cfg, 2, p, final_gain=10.0, fused=fused)
     assert st["cached_steps"] == st["steps"] and st["rows_skipped"] >= (st["steps"] // 2) * 2 * cfg["prompt"]
     print("lockstep prompt caching:", st)
 
 
-def test_lockstep_low_confidence_baseline():
+@FUSED
+def test_lockstep_low_confidence_baseline(fused):
     """The baseline sampler's steps (top-k of a block by confidence, k from the
     schedule) through the same lock-step protocol: 4 blocks, 2 tokens per step."""
     cfg = synth.CONFIGS["tiny"]
     G = cfg["gen"]
     st = lockstep(cfg, 2, None, final_gain=10.0,
-                  driver=lambda B, P, L: LowConfidenceDriver(B, P, L, G // 2, G // 4))
+                  driver=lambda B, P, L: LowConfidenceDriver(B, P, L, G // 2, G // 4), fused=fused)
     assert st["steps"] == G // 2
     print("lockstep low-confidence:", st)
 
@@ -545,4 +559,71 @@ def test_decode_low_confidence(n_steps_div, n_blocks):
         model.decode_low_confidence(tokens.to(DEV), mask.to(DEV), P, n_steps, 5)       # 5 does not divide 64
     with pytest.raises(b.DllmError):
         model.decode_low_confidence(tokens.to(DEV), mask.to(DEV), P, 3, G // 2)        # 3 steps, 2 blocks
+    model.close()
+
+
+# ---- greedy decode fused into the vocabulary projection ----------------------------
+
+@pytest.mark.parametrize("tile", [-1, 1, 2, 3, 4, "fallback"])
+@pytest.mark.parametrize("cfg_name,n_layers,batch,stage", [("tiny", 2, 3, "slow"), ("tiny", 2, 3, "fast"),
+                                                           ("medium", 2, 2, "fast"), ("llada8b", 1, 1, "slow")])
+def test_fused_selector_matches_the_logits_path(cfg_name, n_layers, batch, stage, tile, monkeypatch):
+    """The same step twice from the same state: with bf16 logits and the separate row kernel, and with
+    the greedy decode taken on the projection's accumulators (every tile shape that epilogue is built
+    for, and the register-staged kernel).  Predictions and commits must be identical, confidences
+    equal up to the order of the fp32 sum; both are also checked against the definition (Section 3.1
+    eq. 3: arg max and maximum of the softmax over the vocabulary without [MASK]) evaluated in fp64
+    on the library's own logits.  llada8b: full widths and vocabulary (ragged last column tile, the
+    [MASK] column inside a tile), one layer."""
+    if tile == "fallback":
+        monkeypatch.setenv("DLLM_GEMM_FALLBACK", "1")
+    elif tile >= 0:
+        monkeypatch.setenv("DLLM_GEMM_CFG_E5", str(tile))
+    b = binding()
+    cfg = dict(synth.CONFIGS[cfg_name], n_layers=n_layers)
+    dev = cfg_name == "llada8b"
+    w = synth.make_weights(cfg, device=DEV) if dev else synth.make_weights(cfg)
+    w["final_norm"] = torch.full_like(w["final_norm"], 10.0)      # confidences spread over (0, 1)
+    wd = w if dev else {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in w.items()}
+    mc = synth.model_config(cfg)
+    tokens, mask, prev = synth.make_state(cfg, batch=batch)
+    B, L = tokens.shape
+    P = cfg["prompt"]
+    if stage == "slow":
+        sps = [b.stage_params(b.STAGE_SLOW, P, L - 1, 3, 0.1, 0.9, 1, P, L) for _ in range(B)]
+        lo, hi = P, L - 1
+    else:      # windows that do not touch: one projection per sequence
+        lo, hi = P + 3, P + 3 + (L - P) // 2
+        sps = [b.stage_params(b.STAGE_FAST, lo, hi, 2, 0.1, 0.5, 0, P, L) for _ in range(B)]
+    model = b.Model(mc, wd, B, L)
+    out = b.CommitList(B, L)
+    res = []
+    for fused in (False, True):
+        model.set_fused_selector(fused)
+        t, m, pv = tokens.to(DEV), mask.to(DEV), prev.to(DEV)
+        model.step(t, m, pv, sps, out)
+        torch.cuda.synchronize()
+        pred, conf = (x.view(B, L).clone() for x in model.debug_rows(B * L))
+        logits = model.debug_logits(B * L).view(B, L, -1)[:, lo:hi + 1].clone() if not fused else None
+        res.append((pred, conf, out.to_host(), t.cpu(), m.cpu(), pv.cpu(), logits))
+    rated = torch.zeros(B, L, dtype=torch.bool)
+    rated[:, lo:hi + 1] = mask[:, lo:hi + 1].bool()
+    assert int(rated.sum()) > 0
+    rd = rated.to(DEV)
+    (p0, c0, o0, t0, m0, v0, logits), (p1, c1, o1, t1, m1, v1, _) = res
+    assert torch.equal(p0[rd], p1[rd])
+    assert torch.allclose(c0[rd], c1[rd], rtol=2e-6, atol=0)
+    assert torch.equal(t0, t1) and torch.equal(m0, m1) and torch.equal(v0, v1)
+    for q in range(B):
+        assert o0[q][0] == o1[q][0] and o0[q][1] == o1[q][1] and o0[q][3:] == o1[q][3:]
+        assert np.allclose(o0[q][2], o1[q][2], rtol=2e-6, atol=0)
+    # the definition, on a sample of the rated rows
+    idx = torch.nonzero(rated)
+    idx = idx[torch.randperm(len(idx), generator=torch.Generator().manual_seed(5))[:64]]
+    for q, i in idx.tolist():
+        x = logits[q, i - lo].double()
+        x[mc["mask_id"]] = -float("inf")
+        sm = torch.softmax(x, 0)
+        assert int(p1[q, i]) == int(torch.argmax(x))       # torch returns the first of equal maxima
+        assert abs(float(c1[q, i]) - float(sm.max())) <= 1e-5 * float(sm.max()) + 1e-9
     model.close()
