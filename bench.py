@@ -303,6 +303,14 @@ def main():
             "slow_step_prompt_cached_ms": slow_prompt_cached_ms, "slow_step_rows_recomputed": int(B * L - pskip.sum()),
             "note": "reuse steps read cached keys/values for the positions they leave out; the first timed call of "
                     "each variant follows a cache-filling call"}
+        # the timed step takes the greedy decode inside the vocabulary projection; the same step through
+        # bf16 logits and the separate row kernel, for comparison
+        model.set_fused_selector(False)
+        logits_path_ms = timed_steps(lambda tk, mk, pv: model.step(tk, mk, pv, sps, out))
+        model.set_fused_selector(True)
+        fused_ms = timed_steps(lambda tk, mk, pv: model.step(tk, mk, pv, sps, out))
+        result["slow_step_selector_paths"] = {"fused_into_vocab_projection_ms": fused_ms,
+                                              "through_bf16_logits_ms": logits_path_ms, "rows_rated": B * G}
         # SlowFast decode with both caches on (thresholds as in decode_quantile_thresholds)
         tokens, mask = tokens0.clone(), mask0.clone()
         dpc = b.DecodeParams(10 ** 6, 8, 2, 1, 1, 0, 1.0, tau_min_q, tau_high_q, 1, 8)

@@ -595,8 +595,9 @@ const TileCfg kCfg[kNumCfg] = {
 constexpr int kNumCU = 256;
 constexpr int kLdsPerCU = 160 * 1024;
 // Weight streaming: a workgroup keeps (NST - 1) stages of its W tile in flight and a request takes about
-// 2 us under load, so few or shallow workgroups cannot pull the ~5 TB/s the HBM delivers to this pattern.
-constexpr double kHbmBytesPerUs = 5.0e6, kLoadLatencyUs = 2.0;
+// 2 us under load, so few or shallow workgroups cannot pull the ~4.3 TB/s the HBM delivers to this pattern
+// (measured on the vocabulary projection at M = 256, where every workgroup streams a W tile of its own).
+constexpr double kHbmBytesPerUs = 4.3e6, kLoadLatencyUs = 2.0;
 
 struct Plan {
     int cfg, splits;
