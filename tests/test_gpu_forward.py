@@ -165,7 +165,7 @@ def test_linear_qkv_rope(B, L, H, dh, theta, tile, monkeypatch):
 # ---- attention ------------------------------------------------------------------
 
 @pytest.mark.parametrize("B,L,H,dh", [(1, 96, 4, 64), (2, 200, 2, 128), (1, 64, 1, 64), (1, 129, 2, 128),
-                                      (5, 384, 16, 64),
+                                      (5, 384, 16, 64), (1, 17, 2, 128), (2, 600, 3, 128),
                                       # >= 1024 workgroups: the variant without the in-workgroup key split
                                       (8, 200, 64, 64), (9, 130, 64, 128)])
 def test_attention(B, L, H, dh):

@@ -566,7 +566,9 @@ def test_decode_low_confidence(n_steps_div, n_blocks):
 
 @pytest.mark.parametrize("tile", [-1, 1, 2, 3, 4, "fallback"])
 @pytest.mark.parametrize("cfg_name,n_layers,batch,stage", [("tiny", 2, 3, "slow"), ("tiny", 2, 3, "fast"),
-                                                           ("medium", 2, 2, "fast"), ("llada8b", 1, 1, "slow")])
+                                                           ("medium", 2, 2, "fast"), ("llada8b", 1, 1, "slow"),
+                                                           # vocabulary that ends inside an MFMA tile, [MASK] mid-tile
+                                                           ("tiny_v2040", 2, 2, "slow")])
 def test_fused_selector_matches_the_logits_path(cfg_name, n_layers, batch, stage, tile, monkeypatch):
     """The same step twice from the same state: with bf16 logits and the separate row kernel, and with
     the greedy decode taken on the projection's accumulators (every tile shape that epilogue is built
@@ -580,7 +582,10 @@ def test_fused_selector_matches_the_logits_path(cfg_name, n_layers, batch, stage
     elif tile >= 0:
         monkeypatch.setenv("DLLM_GEMM_CFG_E5", str(tile))
     b = binding()
-    cfg = dict(synth.CONFIGS[cfg_name], n_layers=n_layers)
+    if cfg_name == "tiny_v2040":
+        cfg = dict(synth.CONFIGS["tiny"], n_layers=n_layers, vocab=2040, mask_id=1000)
+    else:
+        cfg = dict(synth.CONFIGS[cfg_name], n_layers=n_layers)
     dev = cfg_name == "llada8b"
     w = synth.make_weights(cfg, device=DEV) if dev else synth.make_weights(cfg)
     w["final_norm"] = torch.full_like(w["final_norm"], 10.0)      # confidences spread over (0, 1)
