@@ -42,8 +42,16 @@ Readings taken where the paper is silent or at odds with itself:
   that fits the same cache: every K_p-th step of a decode (counting from 0) is
   a complete forward that refreshes the keys/values of every position; in the
   steps between, the prompt positions are not recomputed and everyone attends
-  to their cached keys/values.  The response-side half of that scheme
-  (short-interval refresh with value-based selection) is not modelled.
+  to their cached keys/values.
+* Response caching (optional, DecodeParams.response_cache_interval = K_r > 0),
+  the short-interval half of that scheme, in the same simplest form: every
+  K_r-th step of a decode (counting from 0) recomputes the whole response;
+  in the steps between, the response positions outside the range the step
+  rates ([s_cycle, end] in the slow stage, [s_cycle, e_cycle] in the fast
+  stage) are not recomputed.  The first step of a fast stage with out-of-span
+  caching stays a complete forward.  The cited scheme's value-based choice of
+  response positions to refresh between the K_r-th steps is defined outside
+  the paper and is not modelled.
 """
 from __future__ import annotations
 
@@ -101,6 +109,7 @@ class DecodeParams:
     conv_mode: int = 0
     out_of_span_cache: bool = False
     prompt_cache_interval: int = 0     # K_p; 0 = the prompt is recomputed in every step
+    response_cache_interval: int = 0   # K_r; 0 = no response position is left out on this account
 
 
 def active_rows(sp: StageParams, mask: np.ndarray) -> np.ndarray:
@@ -263,6 +272,26 @@ class Controller:
                 self._start_slow()
 
 
+def interval_skip(p: DecodeParams, steps: int, sps: Sequence[StageParams], gen_start: int, gen_end: int, L: int):
+    """Positions the interval caches leave out in step number `steps` (from 0):
+    the prompt unless K_p divides the step number, the response outside each
+    sequence's rated range unless K_r does.  None when both caches are off; an
+    all-zero array (a complete forward that refreshes the cache) on a common
+    multiple."""
+    if p.prompt_cache_interval <= 0 and p.response_cache_interval <= 0:
+        return None
+    also = np.zeros((len(sps), L), dtype=np.uint8)
+    if p.prompt_cache_interval > 0 and steps % p.prompt_cache_interval != 0:
+        also[:, :gen_start] = 1
+    if p.response_cache_interval > 0 and steps % p.response_cache_interval != 0:
+        for b, sp in enumerate(sps):
+            lo, hi = sp.eval_window()
+            for i in range(gen_start, gen_end):
+                if i < lo or i > hi:
+                    also[b, i] = 1
+    return also
+
+
 def decode(predict: Predictor, tokens, mask, gen_start: int, gen_end: int, p: DecodeParams,
            trace: Optional[list] = None) -> int:
     """Full SlowFast decode of a batch, in place; returns the number of
@@ -285,11 +314,7 @@ def decode(predict: Predictor, tokens, mask, gen_start: int, gen_end: int, p: De
         if not live:
             return steps
         skip = [ctl[b].skip for b in range(B)]
-        also = None
-        if p.prompt_cache_interval > 0:
-            also = np.zeros((B, L), dtype=np.uint8)
-            if steps % p.prompt_cache_interval != 0:
-                also[:, :gen_start] = 1
+        also = interval_skip(p, steps, sps, gen_start, gen_end, L)
         res = step(predict, tokens, mask, prev_pred, sps, skip, also)
         steps += 1
         for b in range(B):

@@ -479,3 +479,90 @@ def test_prompt_caching_with_interval_one_is_the_plain_decode():
     # K_p = 4: three of four steps leave the prompt out
     rec = outs[2][2]
     assert all(n == (B * L if i % 4 == 0 else B * (L - cfg["prompt"])) for i, n in enumerate(rec))
+
+
+# ---- response caching (the short-interval half of dLLM-Cache, Section 4.2) ----------
+
+def test_interval_skip_hand_worked():
+    """P = 2, G = 6: K_p = 2, K_r = 3.  Step 0 refreshes both, step 1 leaves out the prompt and the
+    response outside each rated range, step 2 only the response part, step 3 only the prompt, step 6 nothing."""
+    P, L = 2, 8
+    p = sf.DecodeParams(max_steps=99, prompt_cache_interval=2, response_cache_interval=3)
+    slow = sf.StageParams(sf.SLOW, 4, L - 1, 1, 0.1, 0.9, 0, P, L)           # rates [4, 7]
+    fast = sf.StageParams(sf.FAST, 3, 5, 1, 0.1, 0.9, 0, P, L)               # rates [3, 5]
+    idle = sf.StageParams(sf.IDLE, 0, -1, 1, 0.1, 0.9, 0, P, L)              # rates nothing
+    wide = sf.StageParams(sf.FAST, 3, 5, 1, 0.1, 0.9, 0, P, L, sf.CACHE_REFRESH)   # rates [3, 7]
+    sps = [slow, fast, idle, wide]
+    assert sf.interval_skip(sf.DecodeParams(max_steps=99), 1, sps, P, L, L) is None
+    assert not sf.interval_skip(p, 0, sps, P, L, L).any() and not sf.interval_skip(p, 6, sps, P, L, L).any()
+    assert sf.interval_skip(p, 1, sps, P, L, L).tolist() == [[1, 1, 1, 1, 0, 0, 0, 0], [1, 1, 1, 0, 0, 0, 1, 1],
+                                                             [1, 1, 1, 1, 1, 1, 1, 1], [1, 1, 1, 0, 0, 0, 0, 0]]
+    assert sf.interval_skip(p, 2, sps, P, L, L).tolist() == [[0, 0, 1, 1, 0, 0, 0, 0], [0, 0, 1, 0, 0, 0, 1, 1],
+                                                             [0, 0, 1, 1, 1, 1, 1, 1], [0, 0, 1, 0, 0, 0, 0, 0]]
+    assert sf.interval_skip(p, 3, sps, P, L, L).tolist() == [[1, 1, 0, 0, 0, 0, 0, 0]] * 4
+
+
+def test_response_caching_protocol_and_state_independent_trajectory():
+    rng = np.random.default_rng(22)
+    P, G = 4, 30
+    L = P + G
+    conf = (rng.random((2, L)) ** 3).astype(np.float32)
+    pred = rng.integers(0, 50, (2, L)).astype(np.int32)
+    runs = []
+    for kr, kp, oos in ((0, 0, False), (3, 0, False), (2, 5, True), (1, 0, True)):
+        tokens = np.full((2, L), 99, np.int32); mask = np.zeros((2, L), np.uint8); mask[:, P:] = 1
+        rp = RecordingPredictor(conf, pred)
+        trace = []
+        p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.2, tau_high_conf=0.6, out_of_span_cache=oos,
+                            prompt_cache_interval=kp, response_cache_interval=kr)
+        steps = sf.decode(rp, tokens, mask, P, L, p, trace)
+        runs.append((steps, [[r[0] for r in res] for _, res in trace], tokens.copy()))
+        if kr:
+            assert all(c[0] == "cached" for c in rp.calls)
+            skipped = 0
+            for n, ((kind, active, skip), (sps, _)) in enumerate(zip(rp.calls, trace)):
+                assert not (skip & active).any()
+                for q in range(2):
+                    lo, hi = sps[q].eval_window()
+                    outside = np.array([not (lo <= i <= hi) for i in range(P, L)])
+                    if sps[q].cache_mode == sf.CACHE_REFRESH:
+                        assert not skip[q].any()                 # first step of a fast stage: complete
+                    elif n % kr:
+                        assert np.array_equal(skip[q, P:] != 0, outside)
+                        skipped += int(outside.sum())
+                    elif sps[q].cache_mode != sf.CACHE_REUSE:
+                        assert not skip[q, P:].any()             # every K_r-th step recomputes the response
+                    if kp and sps[q].cache_mode != sf.CACHE_REFRESH:
+                        assert skip[q, :P].all() if n % kp else not skip[q, :P].any()
+            assert skipped > 0 or kr == 1
+    for r in runs[1:]:                                   # predictions do not depend on the state here
+        assert r[0] == runs[0][0] and r[1] == runs[0][1] and np.array_equal(r[2], runs[0][2])
+
+
+def test_response_caching_with_interval_one_is_the_plain_decode():
+    from util import OraclePredictor
+    cfg = dict(synth.CONFIGS["tiny"], vocab=257, mask_id=256, prompt=6, gen=16, d_model=64, n_heads=2,
+               head_dim=32, d_ffn=96, n_layers=2)
+    w = synth.make_weights(cfg, std=0.25)
+    outs = []
+    for kr in (0, 1, 3):
+        tokens, mask, _ = synth.make_state(cfg, batch=2)
+        tokens, mask = tokens.numpy().copy(), mask.numpy().copy()
+        B, L = tokens.shape
+        predict = OraclePredictor(synth.model_config(cfg), weights_bits(w), B, L)
+        # confidences of this model sit in 0.08 .. 0.26: spans of one to a few positions, many cycles
+        p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.3, tau_high_conf=0.95, k_max=2, w_hist=1,
+                            response_cache_interval=kr)
+        trace = []
+        steps = sf.decode(predict, tokens, mask, cfg["prompt"], L, p, trace)
+        assert not mask.any() and not (tokens == cfg["mask_id"]).any()
+        outs.append((steps, tokens.copy(), list(predict.recomputed), [sps for sps, _ in trace]))
+    # K_r = 1: every step is a complete forward through the cached path = the plain decode, exactly
+    assert outs[1][0] == outs[0][0] and np.array_equal(outs[1][1], outs[0][1])
+    # K_r = 3: two of three steps recompute the prompt and each sequence's rated range only
+    rec, spss = outs[2][2], outs[2][3]
+    for n, (cnt, sps) in enumerate(zip(rec, spss)):
+        full = B * L
+        part = sum(cfg["prompt"] + max(0, sp.eval_window()[1] - sp.eval_window()[0] + 1) for sp in sps)
+        assert cnt == (full if n % 3 == 0 else part)
+    assert any(c < B * L for c in rec)
