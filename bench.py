@@ -322,6 +322,18 @@ def main():
             "generated_tokens_per_s": B * G / t_c, "steps": steps_c, "seconds": t_c,
             "mean_step_ms": sum(x[4] for x in st_c) / max(len(st_c), 1),
             "params": "as decode_quantile_thresholds, plus out_of_span_cache = 1 and prompt_cache_interval = 8"}
+        # all three caches, intervals as in the paper's Table 4 (K_p = 100, K_r = 5)
+        tokens, mask = tokens0.clone(), mask0.clone()
+        dpa = b.DecodeParams(10 ** 6, 8, 2, 1, 1, 0, 1.0, tau_min_q, tau_high_q, 1, 100, 5)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        steps_a, st_a = model.decode(tokens, mask, P, dpa, stats_capacity=B * G)
+        t_a = time.perf_counter() - t0
+        result["decode_quantile_thresholds_all_caches"] = {
+            "generated_tokens_per_s": B * G / t_a, "steps": steps_a, "seconds": t_a,
+            "mean_step_ms": sum(x[4] for x in st_a) / max(len(st_a), 1),
+            "params": "as decode_quantile_thresholds, plus out_of_span_cache = 1, prompt_cache_interval = 100, "
+                      "response_cache_interval = 5"}
         result["cpu_baseline"] = cpu_baseline_step(mc, weights, tokens0)
         model.close()
         del model, weights

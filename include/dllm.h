@@ -136,6 +136,13 @@ typedef struct {
                                       which the paper combines its sampler with (Section 4.2), in its simplest form:
                                       every K_p-th step (from step 0) is a complete forward that refreshes all cached
                                       keys/values; in the steps between, the prompt positions are not recomputed */
+    int32_t response_cache_interval; /* K_r >= 0.  0: off.  Otherwise the short-interval response caching of that
+                                        scheme, in the same simplest form: every K_r-th step (from step 0) recomputes
+                                        the whole response; in the steps between, the response positions outside the
+                                        range the step rates ([s_cycle, end] in the slow stage, [s_cycle, e_cycle] in
+                                        the fast stage) are not recomputed.  The first step of a fast stage with
+                                        out_of_span_cache stays a complete forward.  The scheme's value-based choice
+                                        of positions to refresh in between is not part of this library */
 } dllm_decode_params;
 
 /* One record per denoising step of dllm_decode. */

@@ -54,7 +54,7 @@ class DecodeParams(C.Structure):
     _fields_ = [("max_steps", C.c_int32), ("k_max", C.c_int32), ("w_hist", C.c_int32), ("k_slow", C.c_int32),
                 ("k_fast", C.c_int32), ("conv_mode", C.c_int32), ("sigma2_stable", C.c_float),
                 ("tau_min_conf", C.c_float), ("tau_high_conf", C.c_float), ("out_of_span_cache", C.c_int32),
-                ("prompt_cache_interval", C.c_int32)]
+                ("prompt_cache_interval", C.c_int32), ("response_cache_interval", C.c_int32)]
 
 
 class StepStat(C.Structure):

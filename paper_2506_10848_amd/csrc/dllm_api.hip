@@ -615,6 +615,7 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
     if (p->out_of_span_cache != 0 && p->out_of_span_cache != 1)
         return fail(h, DLLM_EINVAL, "dllm_decode: out_of_span_cache must be 0 or 1");
     if (p->prompt_cache_interval < 0) return fail(h, DLLM_EINVAL, "dllm_decode: prompt_cache_interval must be >= 0");
+    if (p->response_cache_interval < 0) return fail(h, DLLM_EINVAL, "dllm_decode: response_cache_interval must be >= 0");
     if (stats && stats_capacity < 0) return fail(h, DLLM_EINVAL, "dllm_decode: negative stats_capacity");
 
     Workspace &w = h->ws;
@@ -652,9 +653,10 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
         if (!live) break;
         const bool timed = stats && steps < stats_capacity;
         bool any_cache = false, any_refresh = false;
-        // prompt caching: every K_p-th step recomputes everything, the others leave the prompt out
-        const int kp = p->prompt_cache_interval;
-        const bool prompt_refresh = kp > 0 && steps % kp == 0;
+        // interval caches: every K_p-th step recomputes the prompt, every K_r-th the whole response; the
+        // others leave the prompt / the response outside each sequence's rated range out
+        const int kp = p->prompt_cache_interval, kr = p->response_cache_interval;
+        const bool prompt_refresh = kp > 0 && steps % kp == 0, response_refresh = kr > 0 && steps % kr == 0;
         for (int b = 0; b < B; ++b) {
             uint8_t *sk = skip.data() + (size_t)b * L;
             const int oos = sps[b].stage == DLLM_STAGE_IDLE ? DLLM_CACHE_OFF : ctl[b].cache_mode();
@@ -664,9 +666,18 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
             else
                 memset(sk, 0, L);
             modes[b] = oos;
-            if (kp > 0 && oos != DLLM_CACHE_REFRESH) {
-                if (!prompt_refresh) memset(sk, 1, gen_start);
-                modes[b] = (oos == DLLM_CACHE_REUSE || !prompt_refresh) ? DLLM_CACHE_REUSE : DLLM_CACHE_REFRESH;
+            if ((kp > 0 || kr > 0) && oos != DLLM_CACHE_REFRESH) {
+                if (kp > 0 && !prompt_refresh) memset(sk, 1, gen_start);
+                if (kr > 0 && !response_refresh) {
+                    const bool idle = sps[b].stage == DLLM_STAGE_IDLE;
+                    const int lo = idle ? L : sps[b].s_cycle;
+                    const int hi = idle ? -1 : sps[b].stage == DLLM_STAGE_SLOW ? L - 1 : sps[b].e_cycle;
+                    for (int i = gen_start; i < L; ++i)
+                        if (i < lo || i > hi) sk[i] = 1;
+                }
+                // through the cached path without the wider rated range of an out-of-span refresh step: an
+                // all-zero skip set recomputes every position and refreshes its cache rows
+                modes[b] = DLLM_CACHE_REUSE;
             }
             any_cache |= modes[b] != DLLM_CACHE_OFF;
         }

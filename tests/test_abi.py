@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
 def test_struct_layouts_match_the_header():
     assert C.sizeof(b.Config) == 11 * 4
     assert C.sizeof(b.StageParams) == 9 * 4
-    assert C.sizeof(b.DecodeParams) == 11 * 4
+    assert C.sizeof(b.DecodeParams) == 12 * 4
     assert C.sizeof(b.StepStat) == 5 * 4
     assert C.sizeof(b.CommitListC) == 8 + 7 * 8
 

@@ -93,14 +93,8 @@ class SlowFastDriver:
         self.n = 0
 
     def also(self):
-        """Prompt caching: positions every sequence leaves out in the coming step (None: feature off)."""
-        kp = self.p.prompt_cache_interval
-        if kp <= 0:
-            return None
-        a = np.zeros((len(self.ctl), self.L), np.uint8)
-        if self.n % kp:
-            a[:, :self.P] = 1
-        return a
+        """Prompt / response caching: positions the sequences leave out in the coming step (None: both off)."""
+        return sf.interval_skip(self.p, self.n, self.sps, self.P, self.L, self.L)
 
     def next(self, mask):
         sps = []
@@ -109,6 +103,7 @@ class SlowFastDriver:
             sps.append(sp if sp is not None else
                        sf.StageParams(sf.IDLE, 0, -1, 1, self.p.tau_min_conf, self.p.tau_high_conf, self.p.conv_mode,
                                       self.P, self.L))
+        self.sps = sps
         return sps
 
     def observe(self, sps, res, mask):
@@ -235,7 +230,7 @@ def lockstep(cfg, batch, params, final_gain=1.0, max_checked_steps=10 ** 9, driv
                     sk[s_] = skip[s_]
                 if also is not None and modes[s_] != sf.CACHE_REFRESH:
                     sk[s_] |= also[s_]
-                    modes[s_] = sf.CACHE_REUSE if (sk[s_].any() or modes[s_] == sf.CACHE_REUSE) else sf.CACHE_REFRESH
+                    modes[s_] = sf.CACHE_REUSE      # an all-zero skip set = a complete forward that refreshes the cache
             model.step_cached(g_tok, g_mask, g_prev, csp, modes, sk, out)
             stats["cached_steps"] = stats.get("cached_steps", 0) + 1
             stats["rows_skipped"] = stats.get("rows_skipped", 0) + int(sk.sum())
@@ -387,6 +382,31 @@ def test_lockstep_prompt_caching(fused):
 
 
 @FUSED
+def test_lockstep_prompt_caching_without_out_of_span_caching(fused):
+    """K_p = 3 alone, with the convergence gate on: the steps that refresh the prompt go through the
+    cached path but rate exactly the window of an uncached step (prev_pred outside it must not move)."""
+    cfg = synth.CONFIGS["tiny"]
+    p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.2, tau_high_conf=0.3, conv_mode=1, k_slow=2,
+                        prompt_cache_interval=3)
+    st = lockstep(cfg, 2, p, final_gain=10.0, fused=fused)
+    assert st["cached_steps"] == st["steps"] and st["rows_skipped"] >= (st["steps"] // 2) * 2 * cfg["prompt"]
+    print("lockstep prompt caching only:", st)
+
+
+@FUSED
+@pytest.mark.parametrize("oos,kp,kr", [(False, 0, 3), (True, 4, 2)])
+def test_lockstep_response_caching(oos, kp, kr, fused):
+    """Response caching (K_r) alone and with the other two caches: between the K_r-th steps only the
+    prompt (unless cached too) and each sequence's rated range are recomputed."""
+    cfg = synth.CONFIGS["tiny"]
+    p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.2, tau_high_conf=0.3, conv_mode=1, k_slow=2, k_max=2, w_hist=1,
+                        out_of_span_cache=oos, prompt_cache_interval=kp, response_cache_interval=kr)
+    st = lockstep(cfg, 2, p, final_gain=10.0, fused=fused)
+    assert st["cached_steps"] == st["steps"] and st["rows_skipped"] > 0
+    print(f"lockstep response caching K_r={kr} K_p={kp} oos={oos}:", st)
+
+
+@FUSED
 def test_lockstep_low_confidence_baseline(fused):
     """The baseline sampler's steps (top-k of a block by confidence, k from the
     schedule) through the same lock-step protocol: 4 blocks, 2 tokens per step."""
@@ -400,13 +420,15 @@ def test_lockstep_low_confidence_baseline(fused):
 
 def decode_params(b, p: sf.DecodeParams):
     return b.DecodeParams(p.max_steps, p.k_max, p.w_hist, p.k_slow, p.k_fast, p.conv_mode, p.sigma2_stable,
-                          p.tau_min_conf, p.tau_high_conf, int(p.out_of_span_cache), int(p.prompt_cache_interval))
+                          p.tau_min_conf, p.tau_high_conf, int(p.out_of_span_cache), int(p.prompt_cache_interval),
+                          int(p.response_cache_interval))
 
 
-@pytest.mark.parametrize("cache,kp", [(False, 0), (True, 0), (True, 3), (False, 5)])
+@pytest.mark.parametrize("cache,kp,kr", [(False, 0, 0), (True, 0, 0), (True, 3, 0), (False, 5, 0), (False, 0, 3),
+                                         (True, 4, 2), (False, 3, 1)])
 @pytest.mark.parametrize("gain,tau_min,tau_high,k_max,w_hist", [(10.0, 0.2, 0.3, 8, 2), (10.0, 0.23, 0.999, 1, 1),
                                                                (1.0, None, None, 8, 2)])
-def test_decode_host_controller_matches_the_oracles_controller(cache, kp, gain, tau_min, tau_high, k_max, w_hist):
+def test_decode_host_controller_matches_the_oracles_controller(cache, kp, kr, gain, tau_min, tau_high, k_max, w_hist):
     """dllm_decode's host loop against the oracle's Controller driven by the library's own step
     outputs (same kernels on both sides, so tokens and step counts must be identical): covers the
     stage transitions of Algorithm 1 and the refresh / reuse protocol of out-of-span caching."""
@@ -427,7 +449,8 @@ def test_decode_host_controller_matches_the_oracles_controller(cache, kp, gain, 
         c0 = model.debug_rows(B * L)[1].view(B, L)[mask.bool().to(DEV)].float()
         tau_min, tau_high = float(c0.quantile(0.5)), float(c0.quantile(0.9))
     p = sf.DecodeParams(max_steps=10 ** 6, k_max=k_max, w_hist=w_hist, tau_min_conf=tau_min, tau_high_conf=tau_high,
-                        conv_mode=0, k_slow=1, k_fast=1, out_of_span_cache=cache, prompt_cache_interval=kp)
+                        conv_mode=1 if kr == 3 else 0, k_slow=1, k_fast=1, out_of_span_cache=cache,
+                        prompt_cache_interval=kp, response_cache_interval=kr)
     g_tok, g_mask = tokens.to(DEV), mask.to(DEV)
     steps, stats = model.decode(g_tok, g_mask, P, decode_params(b, p), stats_capacity=4 * G)
     assert int(g_mask.sum()) == 0
@@ -445,15 +468,15 @@ def test_decode_host_controller_matches_the_oracles_controller(cache, kp, gain, 
         csp = [b.stage_params(x.stage, x.s_cycle, x.e_cycle, x.top_k, x.tau_min_conf, x.tau_high_conf, x.conv_mode,
                               x.gen_start, x.gen_end) for x in sps]
         modes = [x.cache_mode for x in sps]
-        if any(modes) or kp:
+        also = sf.interval_skip(p, n, sps, P, L, L)
+        if any(modes) or also is not None:
             sk = np.zeros((B, L), np.uint8)
             for q in range(B):
                 if modes[q] == sf.CACHE_REUSE:
                     sk[q] = ctl[q].skip
-                if kp and modes[q] != sf.CACHE_REFRESH:
-                    if n % kp:
-                        sk[q, :P] = 1
-                    modes[q] = sf.CACHE_REUSE if (sk[q].any() or modes[q] == sf.CACHE_REUSE) else sf.CACHE_REFRESH
+                if also is not None and modes[q] != sf.CACHE_REFRESH:
+                    sk[q] |= also[q]
+                    modes[q] = sf.CACHE_REUSE
             reuse_rows += int(sk.sum())
             model.step_cached(s_tok, s_mask, s_prev, csp, modes, sk, out)
         else:
@@ -467,7 +490,7 @@ def test_decode_host_controller_matches_the_oracles_controller(cache, kp, gain, 
                 ctl[q].observe(got[q][3], got[q][4], hm[q], conf[q])
         n += 1
     assert n == steps and torch.equal(s_tok.cpu(), g_tok.cpu())
-    print(f"decode cache={cache} gain={gain}: {steps} steps, rows skipped in reuse steps {reuse_rows}")
+    print(f"decode cache={cache} K_p={kp} K_r={kr} gain={gain}: {steps} steps, rows skipped in reuse steps {reuse_rows}")
     if (cache and k_max == 1) or kp:       # (confidences sit in 0.20 .. 0.24 here: 0.23 ends the span mid-region)
         assert reuse_rows > 0
     model.close()
