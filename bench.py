@@ -202,7 +202,8 @@ def main():
         traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
 
     result = {
-        "metric": "tokens/s per denoising step (B*L/t_step), LLaDA-8B shape L=512",
+        "metric": "tokens/s per denoising step (B*L/t_step), LLaDA-8B shape L=512" if args.workload == "llada8b"
+                  else f"tokens/s per denoising step (B*L/t_step), workload {args.workload}",
         "value": B * L / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
@@ -212,7 +213,9 @@ def main():
                    "global_batch": B, "seq_len": L},
         "step_tflops": flops / 1e12,
         "step_mfma_frac": flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "roofline": {"kernel": "gemm_il_kernel<256,192,2x2 waves,BK 32,5 stages,SwiGLU> (gate/up projection, one launch per layer)",
+        "roofline": {"kernel": ("gemm_il_kernel<256,192,2x2 waves,BK 32,5 stages,SwiGLU>" if B * L == 512 else
+                                "gemm_il_kernel<tile picked by the planner for this M,SwiGLU>")
+                               + " (gate/up projection, one launch per layer)",
                      "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
                      "avg_launch_ms": k_avg_ms, "launches": k_launches, "flops_per_launch": k_flops},

@@ -580,15 +580,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *
 // ---- host side ----------------------------------------------------------------
 
 // Tile shapes with the modelled cost of one 64-deep K-step and of the epilogue in
-// microseconds when every CU holds a workgroup (measured on MI355X at M = 512 with
-// random operands; under that load the shader clock sits near 1.5 GHz).
+// microseconds when every CU holds a workgroup (measured on MI355X with random
+// operands; under that load the shader clock sits near 1.5 GHz; the three 256-row
+// tiles are fitted to many-round runs at M = 4096 and 12288 as well as to M = 512:
+// per round of 64 K-steps the 256x256 tile takes 115-120 us, 256x192 99-105 us,
+// 256x128 66-77 us, so the largest tile is the cheapest per flop once M fills it).
 struct TileCfg {
     int bm, bn, bk, nst, wn;  // wn: wave columns of the tile
     float step_us, epi_us;
 };
 constexpr int kNumCfg = 7;
 const TileCfg kCfg[kNumCfg] = {
-    {256, 256, 32, 4, 2, 1.85f, 9.0f}, {256, 192, 32, 5, 2, 1.40f, 8.0f}, {256, 128, 64, 3, 2, 0.88f, 6.0f},
+    {256, 256, 32, 4, 2, 1.70f, 9.0f}, {256, 192, 32, 5, 2, 1.45f, 8.0f}, {256, 128, 64, 3, 2, 0.97f, 6.0f},
     {256, 96, 64, 3, 1, 0.77f, 5.0f},  {128, 128, 64, 4, 2, 0.62f, 3.5f}, {128, 64, 64, 4, 2, 1.00f, 2.5f},
     {64, 64, 64, 8, 2, 0.30f, 1.5f},  // few rows (cached steps): a deep ring keeps 56 KB of weights in flight per workgroup
 };
