@@ -97,14 +97,20 @@ __device__ __forceinline__ void wait_stages_after(int n)
     }
 }
 
-// tile of this workgroup; tiles that share W rows get ids congruent mod 8
+// tile of this workgroup; tiles that share W rows get ids congruent mod 8 (the same XCD, one L2).
+// Inside an XCD the workgroups that run together (consecutive local ids) cover kGroupM row tiles
+// times a few column tiles, so that the L2 serves few distinct A and W slices at a time (with two
+// row tiles, M = 512, this is "all row tiles of a column tile, then the next column tile").
+constexpr int kGroupM = 4;
 __device__ __forceinline__ void tile_of(int pid, int num_m, int num_n, int &pid_m, int &pid_n)
 {
     const int n8 = num_n & ~7, head = num_m * n8;
     if (pid < head) {
-        const int xcd = pid & 7, j = pid >> 3;
-        pid_m = j % num_m;
-        pid_n = (j / num_m) * 8 + xcd;
+        const int xcd = pid & 7, j = pid >> 3, nt = n8 >> 3;  // local id; column tiles of this XCD
+        const int in_group = kGroupM * nt, group = j / in_group, r = j - group * in_group;
+        const int first_m = group * kGroupM, gm = min(num_m - first_m, kGroupM);
+        pid_m = first_m + r % gm;
+        pid_n = (r / gm) * 8 + xcd;
     } else {
         const int r = pid - head;
         pid_m = r % num_m;

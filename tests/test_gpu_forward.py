@@ -54,6 +54,7 @@ GEMM_SHAPES = [  # M, N, K
     (100, 200, 72),      # ragged everywhere
     (300, 520, 1024),    # several tiles + tails in M and N
     (512, 1024, 512),
+    (1400, 1100, 128),   # 6 to 22 row tiles by 5 to 18 column tiles: ragged row groups, XCD-mapped head and plain tail
 ]
 
 
