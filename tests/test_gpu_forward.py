@@ -144,7 +144,7 @@ def test_rope(B, L, H, dh, theta):
 
 
 @pytest.mark.parametrize("B,L,H,dh,theta", [(1, 96, 4, 64, 1e4), (2, 70, 3, 128, 5e5), (1, 300, 5, 128, 5e5)])
-@pytest.mark.parametrize("tile", [-1, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6])
 def test_linear_qkv_rope(B, L, H, dh, theta, tile, monkeypatch):
     """QKV projection with the rotary embedding in its epilogue, every tile shape that has it:
     the rotation acts on the fp32 accumulators, so the reference rotates the unrounded product."""
