@@ -53,7 +53,7 @@ __device__ __forceinline__ int k_swz(int row)
 }
 
 template <int DH, int KVSPLIT>
-__global__ __launch_bounds__(kThreads) void attention_kernel(const uint16_t *__restrict__ qsrc,
+__global__ __launch_bounds__(kThreads, 2) void attention_kernel(const uint16_t *__restrict__ qsrc,
                                                              const uint16_t *__restrict__ kvsrc,
                                                              uint16_t *__restrict__ out, int L, int H, int nq,
                                                              SeqRows rows)
