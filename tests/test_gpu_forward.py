@@ -112,7 +112,7 @@ def test_linear_full_size_sampled():
 
 # ---- residual add + RMSNorm --------------------------------------------------
 
-@pytest.mark.parametrize("M,d,n", [(96, 256, 0), (50, 1024, 3), (16, 4096, 8)])
+@pytest.mark.parametrize("M,d,n", [(96, 256, 0), (50, 1024, 3), (16, 4096, 8), (20, 2048, 2), (7, 3000, 1), (8, 5120, 4)])
 def test_add_rmsnorm(M, d, n):
     b = binding()
     g = torch.Generator().manual_seed(3)
