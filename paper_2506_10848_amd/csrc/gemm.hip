@@ -38,15 +38,18 @@
 // zero fill, two LDS stages.
 //
 // Epilogues: bf16 store; fp32 slabs for split-K, which the next residual-add +
-// RMSNorm kernel sums; and two "paired" epilogues, SwiGLU and rotary embedding,
-// that combine two output columns.  For those the W rows of a tile are permuted
+// RMSNorm kernel sums; row statistics (maximum, sum of exponentials and arg max
+// of every row over each wave's column slice: the greedy decode of Section 3.1
+// eq. 3 on the vocabulary projection, which then writes no logits); and two
+// "paired" epilogues, SwiGLU and rotary embedding, that combine two output columns.  For those the W rows of a tile are permuted
 // while they are copied: every 32-row MFMA tile holds 16 first partners (gate
 // rows; first half of a head) followed by their 16 second partners (up rows;
 // second half of the head), so both values of a pair end up in the same lane,
 // 8 accumulator elements apart, whatever the wave layout.
 //
 // Workgroup ids are mapped so that the tiles sharing a weight column block run on
-// the same XCD (ids congruent mod 8 share an L2).
+// the same XCD (ids congruent mod 8 share an L2), and the workgroups of an XCD that
+// run together cover a few row tiles times a few column tiles (see tile_of).
 #include <stdio.h>
 #include <stdlib.h>
 
