@@ -253,6 +253,15 @@ def test_forward_medium_config():
     logits_close(got, ref)
 
 
+def test_forward_maximum_sequence_length_sampled_rows():
+    """L = 8192, the longest sequence the library takes (128 key tiles per query, the rotary table's
+    last row), tiny widths, one layer."""
+    cfg = dict(synth.CONFIGS["tiny"], n_layers=1, prompt=4096, gen=4096)
+    rows = np.array([0, 1, 4095, 4096, 8000, 8191])
+    got, ref = run_forward(cfg, 1, rows=rows)
+    logits_close(got, ref)
+
+
 def test_forward_llada8b_shape_two_layers_sampled_rows():
     """Full LLaDA-8B widths, vocabulary and L = 512 (so every kernel runs in the
     launch shape the benchmark times) with 2 of the 32 layers; the oracle

@@ -329,6 +329,16 @@ def test_lockstep_tiny_config_peaked_logits(fused):
 
 
 @FUSED
+def test_lockstep_maximum_batch(fused):
+    """64 sequences, the most one call takes (one window, one commit list slot, one row table entry each)."""
+    cfg = synth.CONFIGS["tiny"]
+    p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.2, tau_high_conf=0.3, conv_mode=1, k_slow=2)
+    st = lockstep(cfg, 64, p, final_gain=10.0, max_checked_steps=3, fused=fused)
+    assert st["steps"] == 3 and st["tokens_checked"] >= 64
+    print("lockstep 64 sequences:", st)
+
+
+@FUSED
 def test_lockstep_medium_config_first_steps(fused):
     cfg = synth.CONFIGS["medium"]
     p = sf.DecodeParams(max_steps=10 ** 6, tau_min_conf=0.1, tau_high_conf=0.9, conv_mode=1)
