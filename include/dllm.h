@@ -153,7 +153,9 @@ typedef struct {
 } dllm_step_stat;
 
 /* Validates the configuration, records the weight pointers and allocates the
- * workspace for max_batch x max_seq on the current device.  `hip_stream` is a
+ * workspace for max_batch x max_seq on the current device (the bf16 logits
+ * buffer, max_batch x max_seq x vocab, and the key/value cache of the cached
+ * steps are allocated by the first call that needs them).  `hip_stream` is a
  * hipStream_t (NULL = the default stream).  Synchronous. */
 int dllm_create(const dllm_config *cfg, const dllm_weights *w, void *hip_stream, dllm_handle **out);
 void dllm_destroy(dllm_handle *h);
@@ -245,7 +247,8 @@ int dllm_decode_low_confidence(dllm_handle *h, int32_t B, int32_t L, int32_t gen
  * the next call on the handle.  logits: bf16 [B*L][vocab] of the last forward
  * (after dllm_step only the rows inside each sequence's window are defined:
  * the vocabulary projection skips rows the selector does not read; and none
- * are written by a step while the fused selector is on);
+ * are written by a step while the fused selector is on: DLLM_ESTATE if no
+ * call on the handle has written logits yet);
  * pred / conf: int32 / float [B*L] of the last row phase (defined at the
  * masked positions of each window only). */
 int dllm_debug_logits(dllm_handle *h, const void **logits);

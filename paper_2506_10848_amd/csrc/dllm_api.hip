@@ -95,6 +95,15 @@ int dev_alloc(dllm_handle *h, T **p, size_t count)
     return DLLM_OK;
 }
 
+// The bf16 logits [max_batch * max_seq][vocab] are by far the largest buffer and only dllm_forward and
+// steps with the fused selector off need them: allocated on first use.
+int ensure_logits(dllm_handle *h)
+{
+    if (h->ws.logits) return DLLM_OK;
+    const size_t M = (size_t)h->cfg.max_batch * h->cfg.max_seq;
+    return dev_alloc(h, &h->ws.logits, M * (size_t)h->cfg.vocab);
+}
+
 // Checks the per-sequence parameters and turns them into kernel windows.
 int build_select_args(dllm_handle *h, int B, int L, const dllm_stage_params *sp, int capacity, SelectArgs *out,
                       const int32_t *cache_mode = nullptr)
@@ -162,6 +171,7 @@ int vocab_rows(dllm_handle *h, long h_row, long abs_row, int n, int L, const uin
                                         c.mask_id, &parts));
         HIP_TRY(h, launch_rowstats_merge(h->stream, w.rowstats, parts, n, (int)abs_row, L, mask, *win, w.pred, w.conf));
     } else {
+        if (int rc = ensure_logits(h)) return rc;
         HIP_TRY(h, launch_gemm(h->stream, kEpiBf16, w.h + h_row * c.d_model, h->lm_head, w.logits + abs_row * (long)c.vocab,
                                n, c.vocab, c.d_model));
     }
@@ -200,6 +210,7 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const Sele
     }
     HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, M, d, c.rms_eps));
     if (!win) {
+        if (int rc = ensure_logits(h)) return rc;
         HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, h->lm_head, w.logits, M, c.vocab, d));
     } else {
         // merge sequences whose windows make one contiguous run of rows (always true for B = 1)
@@ -464,7 +475,6 @@ int dllm_create(const dllm_config *cfg, const dllm_weights *w, void *hip_stream,
     A(dev_alloc(h, &s.att, M * d));
     A(dev_alloc(h, &s.act, M * f));
     A(dev_alloc(h, &s.partials, (size_t)kMaxSplits * M * d));
-    A(dev_alloc(h, &s.logits, M * (size_t)c.vocab));
     A(dev_alloc(h, &s.rowstats, 3 * gemm_rowstats_max_parts(c.vocab) * M));
     A(dev_alloc(h, &s.pred, M));
     A(dev_alloc(h, &s.conf, M));
@@ -825,7 +835,8 @@ int dllm_profile_end(dllm_handle *h, float *total_ms, int32_t *launches)
 int dllm_debug_logits(dllm_handle *h, const void **logits)
 {
     if (!h || !logits) return fail(h, DLLM_EINVAL, "dllm_debug_logits: null argument");
-    if (h->last_B == 0) return fail(h, DLLM_ESTATE, "dllm_debug_logits: no forward pass has run");
+    if (h->last_B == 0 || !h->ws.logits)
+        return fail(h, DLLM_ESTATE, "dllm_debug_logits: no call on this handle has written logits");
     *logits = h->ws.logits;
     return DLLM_OK;
 }

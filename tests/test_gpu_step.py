@@ -665,3 +665,29 @@ def test_fused_selector_matches_the_logits_path(cfg_name, n_layers, batch, stage
         assert int(p1[q, i]) == int(torch.argmax(x))       # torch returns the first of equal maxima
         assert abs(float(c1[q, i]) - float(sm.max())) <= 1e-5 * float(sm.max()) + 1e-9
     model.close()
+
+
+def test_logits_exist_only_after_a_call_that_writes_them():
+    """Steps with the fused selector never write logits (the buffer is not even allocated until
+    dllm_forward or a step with the fused selector off needs it): reading them before is an error."""
+    b = binding()
+    cfg = synth.CONFIGS["tiny"]
+    w = synth.make_weights(cfg)
+    wd = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in w.items()}
+    tokens, mask, prev = (t.to(DEV) for t in synth.make_state(cfg, batch=1))
+    B, L = tokens.shape
+    P = cfg["prompt"]
+    model = b.Model(synth.model_config(cfg), wd, B, L)
+    out = b.CommitList(B, L)
+    sp = [b.stage_params(b.STAGE_SLOW, P, L - 1, 1, 0.1, 0.9, 0, P, L)]
+    model.step(tokens, mask, prev, sp, out)
+    torch.cuda.synchronize()
+    assert out.to_host()[0][5] == cfg["gen"] - 1
+    with pytest.raises(b.DllmError) as e:
+        model.debug_logits(B * L)
+    assert e.value.code == b.ESTATE
+    model.set_fused_selector(False)
+    model.step(tokens, mask, prev, sp, out)
+    torch.cuda.synchronize()
+    assert model.debug_logits(B * L).shape == (B * L, cfg["vocab"]) and out.to_host()[0][5] == cfg["gen"] - 2
+    model.close()
