@@ -22,7 +22,8 @@ struct Workspace {
     uint16_t *qkv = nullptr;     // [M][3d]
     uint16_t *att = nullptr;     // [M][d]
     uint16_t *act = nullptr;     // [M][f]
-    float *partials = nullptr;   // split-K slabs fp32 [kMaxSplits][M][d]
+    float *partials = nullptr;   // split-K slabs fp32 [splits][rows][d], partials_cap floats
+    size_t partials_cap = 0;
     uint16_t *logits = nullptr;  // [M][V]
     float *rowstats = nullptr;   // [3][gemm_rowstats_max_parts(V)][M]: per-slice (max, sum of exp, argmax) of the fused selector
     int32_t *pred = nullptr;     // [M]
@@ -97,6 +98,14 @@ int dev_alloc(dllm_handle *h, T **p, size_t count)
 
 // The bf16 logits [max_batch * max_seq][vocab] are by far the largest buffer and only dllm_forward and
 // steps with the fused selector off need them: allocated on first use.
+int slab_check(dllm_handle *h, int splits, int rows)
+{
+    if ((size_t)splits * rows * h->cfg.d_model > h->ws.partials_cap)
+        return fail(h, DLLM_ESTATE, "%d split-K slabs of %d rows exceed the workspace sized at dllm_create "
+                                    "(was a split count forced after the handle was created?)", splits, rows);
+    return DLLM_OK;
+}
+
 int ensure_logits(dllm_handle *h)
 {
     if (h->ws.logits) return DLLM_OK;
@@ -198,15 +207,17 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const Sele
             HIP_TRY(h, launch_rope(st, w.qkv, w.rope, B, L, c.n_heads, c.head_dim, c.rope_theta));
         }
         HIP_TRY(h, launch_attention(st, w.qkv, w.att, B, L, c.n_heads, c.head_dim));
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, M, d, d));
         pending = gemm_num_splits(M, d, d);
+        if (int rc = slab_check(h, pending, M)) return rc;
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, M, d, d));
         HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->ffn_norm[l], w.h, M, d, c.rms_eps));
         const bool prof = h->prof_on && h->prof_used < h->prof_cap;
         if (prof) HIP_TRY(h, hipEventRecord(h->prof_ev[2 * h->prof_used], st));
         HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, h->w_gate_up[l], w.act, M, 2 * f, d));
         if (prof) HIP_TRY(h, hipEventRecord(h->prof_ev[2 * h->prof_used++ + 1], st));
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, h->w_down[l], w.partials, M, d, f));
         pending = gemm_num_splits(M, d, f);
+        if (int rc = slab_check(h, pending, M)) return rc;
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, h->w_down[l], w.partials, M, d, f));
     }
     HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, M, d, c.rms_eps));
     if (!win) {
@@ -291,12 +302,14 @@ int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, con
             HIP_TRY(h, launch_scatter_kv(st, w.qkv, w.kv_cache[l], w.rows_d, Ma, d));
             HIP_TRY(h, launch_attention_rows(st, w.qkv, w.kv_cache[l], w.att, B, L, c.n_heads, c.head_dim, sr));
         }
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, Ma, d, d));
         pending = gemm_num_splits(Ma, d, d);
+        if (int rc = slab_check(h, pending, Ma)) return rc;
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, Ma, d, d));
         HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->ffn_norm[l], w.h, Ma, d, c.rms_eps));
         HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, h->w_gate_up[l], w.act, Ma, 2 * f, d));
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, h->w_down[l], w.partials, Ma, d, f));
         pending = gemm_num_splits(Ma, d, f);
+        if (int rc = slab_check(h, pending, Ma)) return rc;
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, h->w_down[l], w.partials, Ma, d, f));
     }
     HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, Ma, d, c.rms_eps));
     // logits stay indexed by absolute row; the rows of a window are consecutive among the recomputed ones
@@ -474,7 +487,16 @@ int dllm_create(const dllm_config *cfg, const dllm_weights *w, void *hip_stream,
     A(dev_alloc(h, &s.qkv, M * 3 * d));
     A(dev_alloc(h, &s.att, M * d));
     A(dev_alloc(h, &s.act, M * f));
-    A(dev_alloc(h, &s.partials, (size_t)kMaxSplits * M * d));
+    // slabs: every split count fits up to 4096 rows; beyond that the planner's own choice (few or no splits once
+    // the row tiles alone fill the chip) decides, sampled every 256 rows; slab_check guards each launch
+    size_t slab_rows = (size_t)kMaxSplits * (M < 4096 ? M : 4096);
+    for (size_t m = 4096; m <= M; m = (m + 256 <= M || m == M) ? m + 256 : M) {
+        const size_t so = (size_t)gemm_num_splits((int)m, (int)d, (int)d), sd = (size_t)gemm_num_splits((int)m, (int)d, (int)f);
+        const size_t need = (so > sd ? so : sd) * m;
+        if (need > slab_rows) slab_rows = need;
+    }
+    s.partials_cap = slab_rows * d;
+    A(dev_alloc(h, &s.partials, s.partials_cap));
     A(dev_alloc(h, &s.rowstats, 3 * gemm_rowstats_max_parts(c.vocab) * M));
     A(dev_alloc(h, &s.pred, M));
     A(dev_alloc(h, &s.conf, M));
