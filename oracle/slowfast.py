@@ -1,8 +1,15 @@
 """SlowFast selection rule, stage controller and decode loop -- CPU oracle.
 
 TEST INFRASTRUCTURE: plain Python over small arrays, written from Section 3.3
-("SlowFast Sampling") and Algorithm 1 of the paper, in the paper's order and
-notation.  It imports nothing from the HIP library.
+("SlowFast Sampling") and Algorithm 1 of the paper.  It imports nothing from
+the HIP library.
+
+Algorithm 1 appears twice, in two shapes that are checked against each other:
+`alg1_sequence` / `decode_alg1` take its steps in the paper's order, as the
+nested loops of the listing (outer cycle loop, exploratory loop, accelerated
+loop) for one sequence; `Controller` / `decode` is the same method turned
+inside out into a per-sequence state machine, which is what a batch that shares
+one forward pass per step needs.
 
 Positions are absolute and 0-based; a span [s, e] is inclusive at both ends.
 The generated region is [gen_start, gen_end) and the prompt is never masked.
@@ -322,6 +329,156 @@ def decode(predict: Predictor, tokens, mask, gen_start: int, gen_end: int, p: De
                 ctl[b].observe(res[b][3], res[b][4], mask[b], res[b][6])
         if trace is not None:
             trace.append((sps, res))
+
+
+def alg1_sequence(tokens, mask, prev_pred, gen_start: int, gen_end: int, p: DecodeParams, log: Optional[list] = None):
+    """Algorithm 1 for ONE sequence, as the listing's nested loops, in place on
+    tokens / mask / prev_pred (1-D arrays over the L positions).
+
+    A generator: every "Predict r_0 and confidence" line of the listing is a
+    `yield (stage params, cached set or None)` that must be answered (`send`)
+    with (pred [L], conf [L]) valid at the masked positions of the step's
+    evaluation window.  Everything else -- cautious decoding, end-point
+    prediction, stability check, fallback, in-span decoding, out-of-span
+    caching, cycle advance -- is written out below in the listing's order,
+    with the readings of the module docstring marked where they enter.
+    log (optional) receives one (stage, s_cycle, e_cycle, commit positions) per step."""
+    L = len(mask)
+    k = p.max_steps                                   # k <- N
+    s_cycle = gen_start                               # s_cycle <- first generated position
+    tau_min, tau_high = np.float32(p.tau_min_conf), np.float32(p.tau_high_conf)
+
+    def masked(lo, hi):                               # masked positions of [lo, hi]
+        return [i for i in range(max(lo, 0), min(hi, L - 1) + 1) if mask[i]]
+
+    def unmask(commit, pred, rated):
+        for i in commit:                              # transition: unmask, never re-mask
+            tokens[i] = pred[i]
+            mask[i] = 0
+        for i in rated:                               # this step's estimate, for the convergence gate
+            prev_pred[i] = pred[i]
+
+    # "while k > 0 and s_cycle < L": every mask lies in [s_cycle, gen_end), so "a mask is left" is the same test
+    while k > 0 and masked(s_cycle, gen_end - 1):
+        # ---- Phase 1: exploratory stage (slow) ----
+        H_W: List[int] = []                           # reading: the history starts empty in every exploratory stage
+        step_count = 0
+        is_stable = False
+        e_cycle = e_k = None
+        while step_count < p.k_max and k > 0 and masked(s_cycle, gen_end - 1):
+            sp = StageParams(SLOW, s_cycle, gen_end - 1, p.k_slow, p.tau_min_conf, p.tau_high_conf, p.conv_mode,
+                             gen_start, gen_end)
+            pred, conf = yield sp, None               # predict r_0 and its confidence
+            conf = np.asarray(conf, dtype=np.float32)
+            window = masked(s_cycle, gen_end - 1)     # the state before this step's commits
+            # cautious decoding: the k_slow most confident positions of [s_cycle, end] (ties: lower position)
+            commit = sorted(sorted(window, key=lambda i: (-float(conf[i]), i))[:p.k_slow])
+            # end point prediction (eq. 6); reading: nothing above tau_min -> the leftmost mask of the window
+            above = [i for i in window if conf[i] > tau_min]
+            e_k = max(above) if above else window[0]
+            H_W = (H_W + [e_k])[-p.w_hist:]           # sliding window of the last W_hist candidates
+            unmask(commit, pred, window)
+            if log is not None:
+                log.append((SLOW, s_cycle, gen_end - 1, commit))
+            k -= 1
+            step_count += 1
+            # stability check (eq. 7): population variance, strictly below the threshold
+            mean = sum(H_W) / len(H_W)
+            var = sum((h - mean) ** 2 for h in H_W) / len(H_W)
+            if len(H_W) >= p.w_hist and var < p.sigma2_stable:
+                is_stable = True
+                e_cycle = sum(H_W) // len(H_W)        # eq. 8, floored
+                break
+        if e_k is None:                               # no exploratory step ran (k exhausted)
+            break
+        if not is_stable:
+            e_cycle = e_k                             # fallback if no convergence: the last candidate
+        e_cycle = min(max(e_cycle, s_cycle), gen_end - 1)
+
+        # ---- Phase 2: accelerated decoding stage (fast) ----
+        # reading: repeated until no mask is left in [s_cycle, e_cycle] (a span that the slow steps
+        # already emptied costs no forward pass)
+        cached = None
+        first_of_stage = True
+        while k > 0 and masked(s_cycle, e_cycle):
+            mode = CACHE_OFF
+            if p.out_of_span_cache:
+                mode = CACHE_REFRESH if first_of_stage else CACHE_REUSE
+            sp = StageParams(FAST, s_cycle, e_cycle, p.k_fast, p.tau_min_conf, p.tau_high_conf, p.conv_mode,
+                             gen_start, gen_end, mode)
+            pred, conf = yield sp, cached             # predict r_0 and its confidence
+            conf = np.asarray(conf, dtype=np.float32)
+            span = masked(s_cycle, e_cycle)
+            if p.out_of_span_cache and first_of_stage:
+                # out-of-span caching: masked positions right of the span whose confidence in this
+                # complete prediction is below tau_min keep their features for the rest of the stage
+                cached = np.zeros(L, dtype=np.uint8)
+                for i in masked(e_cycle + 1, gen_end - 1):
+                    if conf[i] < tau_min:
+                        cached[i] = 1
+            # in-span parallel decoding (eq. 9), with the token-level convergence gate when conv_mode = 1
+            s_high = [i for i in span if conf[i] > tau_high
+                      and (p.conv_mode == 0 or int(pred[i]) == int(prev_pred[i]))]
+            if s_high:
+                commit = s_high                       # aggressive unmasking
+            else:                                     # fallback refinement: top-k_fast of the span
+                commit = sorted(sorted(span, key=lambda i: (-float(conf[i]), i))[:p.k_fast])
+            lo, hi = sp.eval_window()
+            unmask(commit, pred, masked(lo, hi))
+            if log is not None:
+                log.append((FAST, s_cycle, e_cycle, commit))
+            k -= 1
+            first_of_stage = False
+        s_cycle = e_cycle + 1                         # advance the stable region start
+
+
+def decode_alg1(predict: Predictor, tokens, mask, gen_start: int, gen_end: int, p: DecodeParams,
+                trace: Optional[list] = None) -> int:
+    """Full decode of a batch by running `alg1_sequence` once per sequence; the
+    sequences whose generators ask for a prediction share one forward pass per
+    step, the finished ones ride along idle.  In place; returns the number of
+    forward passes.  trace (optional) receives one list per step with, per
+    sequence, (stage, s_cycle, e_cycle, commit positions) or None when idle.
+    The interval caches of DecodeParams (K_p, K_r) act on the forward pass only
+    and are applied here, outside Algorithm 1, exactly as `decode` applies them."""
+    B, L = tokens.shape
+    prev_pred = np.full((B, L), -1, dtype=np.int32)
+    logs: List[list] = [[] for _ in range(B)]
+    gens = [alg1_sequence(tokens[b], mask[b], prev_pred[b], gen_start, gen_end, p, logs[b]) for b in range(B)]
+    asks: List[Optional[tuple]] = []
+    for g in gens:                                    # run every sequence up to its first prediction
+        try:
+            asks.append(next(g))
+        except StopIteration:
+            asks.append(None)
+    idle = StageParams(IDLE, 0, -1, 1, p.tau_min_conf, p.tau_high_conf, p.conv_mode, gen_start, gen_end)
+    steps = 0
+    while any(a is not None for a in asks):
+        sps = [a[0] if a is not None else idle for a in asks]
+        active = np.stack([active_rows(sps[b], mask[b]) for b in range(B)])
+        also = interval_skip(p, steps, sps, gen_start, gen_end, L)
+        if any(sp.cache_mode != CACHE_OFF for sp in sps) or also is not None:
+            sk = np.zeros((B, L), dtype=np.uint8)
+            for b in range(B):
+                if sps[b].cache_mode == CACHE_REUSE:
+                    sk[b] = asks[b][1]
+                if also is not None and sps[b].cache_mode != CACHE_REFRESH:
+                    sk[b] |= also[b]
+            pred, conf = predict.cached(tokens, active, sk)
+        else:
+            pred, conf = predict(tokens, active)
+        steps += 1
+        done_before = [len(lg) for lg in logs]
+        for b in range(B):
+            if asks[b] is None:
+                continue
+            try:
+                asks[b] = gens[b].send((pred[b], conf[b]))
+            except StopIteration:
+                asks[b] = None
+        if trace is not None:
+            trace.append([logs[b][done_before[b]] if len(logs[b]) > done_before[b] else None for b in range(B)])
+    return steps
 
 
 def n_unmasked_target(length: int, n_steps: int, j: int) -> int:

@@ -566,3 +566,119 @@ def test_response_caching_with_interval_one_is_the_plain_decode():
         part = sum(cfg["prompt"] + max(0, sp.eval_window()[1] - sp.eval_window()[0] + 1) for sp in sps)
         assert cnt == (full if n % 3 == 0 else part)
     assert any(c < B * L for c in rec)
+
+
+# ---- Algorithm 1 as nested loops (alg1_sequence / decode_alg1) ---------------------
+# Pinned by hand-worked runs, then held against the state-machine form (Controller / decode):
+# the two are written in different shapes, so a misreading has to be made twice to go unseen.
+
+def run_alg1(conf, pred, P, L, p):
+    B = conf.shape[0]
+    tokens = np.full((B, L), 999, np.int32); mask = np.zeros((B, L), np.uint8); mask[:, P:] = 1
+    trace = []
+    steps = sf.decode_alg1(RecordingPredictor(conf, pred), tokens, mask, P, L, p, trace)
+    return steps, trace, tokens, mask
+
+
+def test_alg1_hand_worked_stable_cycle():
+    # confident block 2..7, the rest below tau_min; Section 3.3 step by step:
+    #  slow: top-1 of [2, 13] is position 2 (ties -> lower position), e_cand = 7
+    #  slow: commits 3, e_cand = 7 -> H = {7, 7}, variance 0 < 1 -> e_cycle = 7
+    #  fast: masks 4..7 of [2, 7] all exceed 0.9 and repeat their prediction -> committed together
+    #  then nothing exceeds tau_min: e_cand = leftmost mask; cycles of two slow steps whose spans are
+    #  already clean when they end (H = {8, 9} -> floor(8.5) = 8, H = {10, 11} -> 10, H = {12, 13} -> 12)
+    P, L = 2, 14
+    conf = np.full((1, L), 0.05, np.float32); conf[0, 2:8] = 0.95
+    pred = np.arange(L, dtype=np.int32)[None] + 200
+    p = sf.DecodeParams(max_steps=100, tau_min_conf=0.1, tau_high_conf=0.9, conv_mode=1)
+    steps, trace, tokens, mask = run_alg1(conf, pred, P, L, p)
+    end = L - 1
+    assert [t[0] for t in trace] == [
+        (sf.SLOW, 2, end, [2]), (sf.SLOW, 2, end, [3]), (sf.FAST, 2, 7, [4, 5, 6, 7]),
+        (sf.SLOW, 8, end, [8]), (sf.SLOW, 8, end, [9]),
+        (sf.SLOW, 9, end, [10]), (sf.SLOW, 9, end, [11]),
+        (sf.SLOW, 11, end, [12]), (sf.SLOW, 11, end, [13])]
+    assert steps == 9 and not mask.any() and np.array_equal(tokens[0, P:], pred[0, P:])
+
+
+def test_alg1_hand_worked_kmax_fallback_and_fast_fallback():
+    # e_cand walks 9, 7, 5 (each is committed by the step that reports it): windows {9,7} and {7,5}
+    # have variance 1, not < 1, so K_max = 3 ends the stage with the LAST candidate, e_cycle = 5;
+    # nothing in [1, 5] reaches tau_high, so every fast step falls back to the top-1 of the span.
+    P, L = 1, 10
+    conf = np.full((1, L), 0.05, np.float32)
+    conf[0, 9], conf[0, 7], conf[0, 5], conf[0, 3] = 0.5, 0.4, 0.3, 0.2
+    pred = np.arange(L, dtype=np.int32)[None]
+    p = sf.DecodeParams(max_steps=100, k_max=3, w_hist=2, sigma2_stable=1.0, tau_min_conf=0.1, tau_high_conf=0.9)
+    steps, trace, tokens, mask = run_alg1(conf, pred, P, L, p)
+    assert [t[0] for t in trace] == [
+        (sf.SLOW, 1, 9, [9]), (sf.SLOW, 1, 9, [7]), (sf.SLOW, 1, 9, [5]),
+        (sf.FAST, 1, 5, [3]), (sf.FAST, 1, 5, [1]), (sf.FAST, 1, 5, [2]), (sf.FAST, 1, 5, [4]),
+        (sf.SLOW, 6, 9, [6]), (sf.SLOW, 6, 9, [8])]
+    assert steps == 9 and not mask.any()
+    # N = 4 stops after the first fast step
+    p4 = sf.DecodeParams(max_steps=4, k_max=3, w_hist=2, sigma2_stable=1.0, tau_min_conf=0.1, tau_high_conf=0.9)
+    steps, trace, tokens, mask = run_alg1(conf, pred, P, L, p4)
+    assert steps == 4 and [t[0][0] for t in trace] == [sf.SLOW, sf.SLOW, sf.SLOW, sf.FAST] and mask.sum() == 5
+
+
+def state_machine_trace(trace):
+    """decode()'s trace in the shape of decode_alg1's."""
+    out = []
+    for sps, res in trace:
+        out.append([None if sp.stage == sf.IDLE else (sp.stage, sp.s_cycle, sp.window()[1], r[0])
+                    for sp, r in zip(sps, res)])
+    return out
+
+
+@pytest.mark.parametrize("k_max,w_hist,sigma2", [(8, 2, 1.0), (1, 1, 1.0), (3, 3, 0.23), (4, 2, 30.0), (2, 4, 1.0)])
+@pytest.mark.parametrize("tau_min,tau_high,conv,k_slow,k_fast", [(0.2, 0.6, 0, 1, 1), (0.1, 0.9, 1, 2, 3),
+                                                                 (-1.0, 1.0, 0, 1, 1), (0.5, 0.5, 1, 3, 1)])
+@pytest.mark.parametrize("cache", [False, True])
+def test_alg1_loops_and_state_machine_agree_on_state_independent_confidences(k_max, w_hist, sigma2, tau_min, tau_high,
+                                                                             conv, k_slow, k_fast, cache):
+    rng = np.random.default_rng(100 * k_max + w_hist)
+    P, G, B = 3, 37, 3
+    L = P + G
+    conf = (rng.random((B, L)) ** 2).astype(np.float32)
+    conf[1, P + 5:P + 20] = 0.97                       # a confident region in one sequence
+    pred = rng.integers(0, 50, (B, L)).astype(np.int32)
+    for max_steps in (10 ** 6, 7):
+        p = sf.DecodeParams(max_steps=max_steps, k_max=k_max, w_hist=w_hist, sigma2_stable=sigma2, tau_min_conf=tau_min,
+                            tau_high_conf=tau_high, k_slow=k_slow, k_fast=k_fast, conv_mode=conv, out_of_span_cache=cache)
+        s1, t1, tok1, m1 = run_alg1(conf, pred, P, L, p)
+        tok2 = np.full((B, L), 999, np.int32); m2 = np.zeros((B, L), np.uint8); m2[:, P:] = 1
+        t2 = []
+        rp = RecordingPredictor(conf, pred)
+        s2 = sf.decode(rp, tok2, m2, P, L, p, t2)
+        assert s1 == s2 and t1 == state_machine_trace(t2)
+        assert np.array_equal(tok1, tok2) and np.array_equal(m1, m2)
+
+
+@pytest.mark.parametrize("cache,kp,kr", [(False, 0, 0), (True, 0, 0), (True, 3, 2), (False, 0, 3)])
+def test_alg1_loops_and_state_machine_agree_on_a_small_model(cache, kp, kr):
+    """State-dependent predictions (and stale cached features): the two forms must ask the predictor
+    for the same steps, with the same cached sets, and end in the same tokens."""
+    cfg = dict(synth.CONFIGS["tiny"], vocab=257, mask_id=256, prompt=6, gen=20, d_model=64, n_heads=2,
+               head_dim=32, d_ffn=96, n_layers=1)
+    w = synth.make_weights(cfg, std=0.25)
+    mc = synth.model_config(cfg)
+    P, L = cfg["prompt"], cfg["prompt"] + cfg["gen"]
+    tok0, mask0, _ = synth.make_state(cfg, batch=2)
+    from util import OraclePredictor
+    c0 = OraclePredictor(mc, weights_bits(w), 2, L)(tok0.numpy(), mask0.numpy())[1]
+    tau_min, tau_high = float(np.quantile(c0[mask0.numpy() == 1], 0.4)), float(np.quantile(c0[mask0.numpy() == 1], 0.8))
+    p = sf.DecodeParams(max_steps=10 ** 6, k_max=3, tau_min_conf=tau_min, tau_high_conf=tau_high, conv_mode=1,
+                        out_of_span_cache=cache, prompt_cache_interval=kp, response_cache_interval=kr)
+    runs = []
+    for fn in (sf.decode_alg1, sf.decode):
+        tokens, mask = tok0.numpy().copy(), mask0.numpy().copy()
+        pr = OraclePredictor(mc, weights_bits(w), 2, L)
+        trace = []
+        steps = fn(pr, tokens, mask, P, L, p, trace)
+        runs.append((steps, trace if fn is sf.decode_alg1 else state_machine_trace(trace), tokens, pr.recomputed))
+    assert runs[0][0] == runs[1][0] and runs[0][1] == runs[1][1]
+    assert np.array_equal(runs[0][2], runs[1][2]) and runs[0][3] == runs[1][3]
+    assert not (runs[0][2] == cfg["mask_id"]).any()
+    if cache or kp or kr:
+        assert min(runs[0][3]) < 2 * L            # some step really left positions out
