@@ -167,7 +167,11 @@ const char *dllm_last_error(const dllm_handle *h);
  *   tokens[pos] <- prediction, mask[pos] <- 0            at committed positions
  *   prev_pred[i] <- prediction                           at every masked position of the window
  * Committed tokens are never re-masked.  Logits never leave the library.
- *   tokens    dev int32 [B][L]  in/out
+ *   tokens    dev int32 [B][L]  in/out; every id must lie in [0, vocab).  The ids live on the device,
+ *                               so the host cannot check them before enqueueing: an id outside the range
+ *                               is never used as an index (its position gets an all-zero embedding) and
+ *                               raises a flag that dllm_decode / dllm_decode_low_confidence (after every
+ *                               step) and dllm_sync_status turn into DLLM_EINVAL
  *   mask      dev uint8 [B][L]  in/out, 1 = [MASK]
  *   prev_pred dev int32 [B][L]  in/out, -1 = no previous prediction
  *   sp        host [B]
@@ -178,6 +182,11 @@ const char *dllm_last_error(const dllm_handle *h);
  * its window is not an error: n_commit = 0. */
 int dllm_step(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *mask, int32_t *prev_pred,
               const dllm_stage_params *sp, const dllm_commit_list *out);
+
+/* Waits for the handle's stream and reports what only the device could see: DLLM_EINVAL if a step or
+ * forward since the last report read a token id outside [0, vocab) (Section 3.1: the state y^(k) is a
+ * sequence over the vocabulary; see `tokens` above), else DLLM_OK.  Reporting clears the condition. */
+int dllm_sync_status(dllm_handle *h);
 
 /* Where the greedy decode and the confidence (Section 3.1, eq. 3 and the confidence it defines)
  * of dllm_step / dllm_step_cached / the decode calls are computed.  enable != 0 (the default):
@@ -252,6 +261,18 @@ int dllm_decode_low_confidence(dllm_handle *h, int32_t B, int32_t L, int32_t gen
  * pred / conf: int32 / float [B*L] of the last row phase (defined at the
  * masked positions of each window only). */
 int dllm_debug_logits(dllm_handle *h, const void **logits);
+/* Test hook: the library reads its DLLM_GEMM_* / DLLM_NO_FUSED_ROPE environment switches (kernel and
+ * tile selection for tests and tuning) once per process and keeps the launch plan it finds for every
+ * product shape; this reads them again and drops the kept plans.  Not for use while another thread is
+ * inside the library with work that depends on the old values. */
+void dllm_debug_reload_env(void);
+/* Measurement hook (runs on the host only): the launch plan the library uses for the product
+ * C[M][N] = A[M][K] W[N][K]^T with a given epilogue: 0 bf16 output, 1 gate/up + SwiGLU (N counts gate and
+ * up rows), 2 fp32 split-K slabs (O and down projection; split_limit = most slabs allowed, 8 in a step at
+ * up to 4096 rows), 3 / 4 QKV + rotary embedding for head_dim 64 / 128, 5 vocabulary projection with the
+ * greedy decode.  out8 (host): tile rows, tile columns, K depth of a pipeline stage, pipeline stages, wave
+ * grid rows, wave grid columns, K splits, 1 for the asynchronous-copy kernel / 0 for the register-staged one. */
+int dllm_debug_gemm_plan(int32_t epilogue, int32_t M, int32_t N, int32_t K, int32_t split_limit, int32_t *out8);
 int dllm_debug_rows(dllm_handle *h, const int32_t **pred, const float **conf);
 
 /* Measurement hook for the kernel that carries the most flops of a step, the

@@ -62,7 +62,7 @@ class StepStat(C.Structure):
                 ("ms", C.c_float)]
 
 
-EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_step_cached", "dllm_decode", "dllm_decode_low_confidence", "dllm_set_fused_selector", "dllm_debug_logits",
+EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_step_cached", "dllm_decode", "dllm_decode_low_confidence", "dllm_set_fused_selector", "dllm_sync_status", "dllm_debug_reload_env", "dllm_debug_gemm_plan", "dllm_debug_logits",
            "dllm_debug_rows", "dllm_profile_begin", "dllm_profile_end", "dllm_forward", "dllm_select", "dllm_op_linear", "dllm_op_linear_swiglu",
            "dllm_op_add_rmsnorm", "dllm_op_rope", "dllm_op_linear_qkv_rope", "dllm_op_attention"]
 
@@ -82,7 +82,22 @@ def lib() -> C.CDLL:
         _lib.dllm_last_error.argtypes = [C.c_void_p]
         _lib.dllm_destroy.restype = None
         _lib.dllm_destroy.argtypes = [C.c_void_p]
+        _lib.dllm_debug_reload_env.restype = None
+        _lib.dllm_debug_reload_env.argtypes = []
     return _lib
+
+
+def gemm_plan(epilogue: int, M: int, N: int, K: int, split_limit: int = 8) -> dict:
+    """dllm_debug_gemm_plan as a dict (tile, stage depth, stages, wave grid, splits, kernel kind)."""
+    out = (C.c_int32 * 8)()
+    _check(lib().dllm_debug_gemm_plan(epilogue, M, N, K, split_limit, out))
+    keys = ("bm", "bn", "bk", "stages", "waves_m", "waves_n", "splits", "async_copy")
+    return dict(zip(keys, list(out)))
+
+
+def reload_env() -> None:
+    """dllm_debug_reload_env: the library re-reads its DLLM_* environment switches (tests only)."""
+    lib().dllm_debug_reload_env()
 
 
 def _check(rc: int, handle=None):
@@ -206,6 +221,10 @@ class Model:
         cl = out.c_struct()
         _check(lib().dllm_step(self._h, B, L, _ptr(tokens), _ptr(mask), _ptr(prev_pred), _sp_array(sps),
                                C.byref(cl)), self._h)
+
+    def sync_status(self) -> None:
+        """dllm_sync_status: waits for the stream; raises if a step read a token id outside [0, vocab)."""
+        _check(lib().dllm_sync_status(self._h), self._h)
 
     def set_fused_selector(self, enable: bool) -> None:
         """dllm_set_fused_selector: greedy decode inside the vocabulary projection (default) or from bf16 logits."""

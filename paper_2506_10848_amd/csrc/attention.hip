@@ -319,13 +319,10 @@ hipError_t launch_split(hipStream_t stream, const void *q, const void *kv, void 
     static_assert(KVSPLIT == 1 || sizeof(Smem<DH, 2>) >= (2 * (DH / 32) * 16 * 64 + 4 * 64) * sizeof(float),
                   "merge buffer fits");
     auto kern = attention_kernel<DH, KVSPLIT>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    // once per kernel, whichever thread comes first (initialisation of a local static is thread-safe)
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (attr != hipSuccess) return attr;
     const int nq = (max_count + QT - 1) / QT;
     hipLaunchKernelGGL(kern, dim3(nq * H * B), dim3(kThreads), lds, stream, (const uint16_t *)q, (const uint16_t *)kv,
                        (uint16_t *)out, Lk, H, nq, rows);

@@ -31,17 +31,23 @@ struct Workspace {
     float2 *rope = nullptr;      // [max_seq][dh/2]
     // decode-only state
     int32_t *prev_pred = nullptr;  // [M]
-    int32_t *cl_ints = nullptr;    // n_commit, e_cand, first_masked, n_masked_after: 4 x [max_batch]
+    int32_t *cl_ints = nullptr;    // n_commit, e_cand, first_masked, n_masked_after: 4 x [max_batch], then bad_token
+    int32_t *bad_token = nullptr;  // = cl_ints + 4 * max_batch: set by the embedding kernel on an id outside [0, vocab)
     int32_t *cl_pos = nullptr, *cl_tok = nullptr;
     float *cl_conf = nullptr;      // [max_batch][max_seq]
+    // pinned host memory: mask [M] | step results [4 * max_batch + 1] | confidences [M] | 2 x (rows [M], pos [M])
     uint8_t *host_pinned = nullptr;
+    int32_t *host_ints = nullptr;
+    float *host_conf = nullptr;
+    int32_t *host_rows[2] = {nullptr, nullptr};  // row / position lists of cached steps, double-buffered
+    hipEvent_t rows_copied[2] = {nullptr, nullptr};
+    int rows_slot = 0;
     // out-of-span caching: per-layer qkv rows of every position (k and v thirds are the cached features)
     std::vector<uint16_t *> kv_cache;
     int32_t *rows_d = nullptr, *pos_d = nullptr;  // recomputed rows of a step and their positions, [M]
     bool cache_valid = false;
     int cache_B = 0, cache_L = 0;  // batch shape the cache rows belong to
 };
-constexpr int kMaxSplits = 8;
 
 }  // namespace
 
@@ -96,16 +102,16 @@ int dev_alloc(dllm_handle *h, T **p, size_t count)
     return DLLM_OK;
 }
 
-// The bf16 logits [max_batch * max_seq][vocab] are by far the largest buffer and only dllm_forward and
-// steps with the fused selector off need them: allocated on first use.
-int slab_check(dllm_handle *h, int splits, int rows)
+// How many fp32 split-K slabs of `rows` rows the slab workspace holds (0: not even one).  The planner
+// is given this as its limit, so every row count up to max_batch * max_seq gets a plan that fits.
+int slab_limit(const dllm_handle *h, int rows)
 {
-    if ((size_t)splits * rows * h->cfg.d_model > h->ws.partials_cap)
-        return fail(h, DLLM_ESTATE, "%d split-K slabs of %d rows exceed the workspace sized at dllm_create "
-                                    "(was a split count forced after the handle was created?)", splits, rows);
-    return DLLM_OK;
+    const size_t n = h->ws.partials_cap / ((size_t)rows * h->cfg.d_model);
+    return n > (size_t)kGemmMaxSplits ? kGemmMaxSplits : (int)n;
 }
 
+// The bf16 logits [max_batch * max_seq][vocab] are by far the largest buffer and only dllm_forward and
+// steps with the fused selector off need them: allocated on first use.
 int ensure_logits(dllm_handle *h)
 {
     if (h->ws.logits) return DLLM_OK;
@@ -196,7 +202,9 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const Sele
     const int M = B * L, d = c.d_model, f = c.d_ffn;
     Workspace &w = h->ws;
     hipStream_t st = h->stream;
-    HIP_TRY(h, launch_embed(st, tokens, nullptr, h->embed, w.x, M, d));
+    HIP_TRY(h, launch_embed(st, tokens, nullptr, h->embed, w.x, M, d, c.vocab, w.bad_token));
+    const int slabs = slab_limit(h, M);
+    if (slabs < 1) return fail(h, DLLM_ESTATE, "the split-K workspace does not hold one slab of %d rows", M);
     int pending = 0;  // fp32 slabs waiting to be added to the residual stream
     for (int l = 0; l < c.n_layers; ++l) {
         HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->attn_norm[l], w.h, M, d, c.rms_eps));
@@ -207,17 +215,15 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const Sele
             HIP_TRY(h, launch_rope(st, w.qkv, w.rope, B, L, c.n_heads, c.head_dim, c.rope_theta));
         }
         HIP_TRY(h, launch_attention(st, w.qkv, w.att, B, L, c.n_heads, c.head_dim));
-        pending = gemm_num_splits(M, d, d);
-        if (int rc = slab_check(h, pending, M)) return rc;
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, M, d, d));
+        pending = gemm_num_splits(M, d, d, slabs);
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, M, d, d, slabs));
         HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->ffn_norm[l], w.h, M, d, c.rms_eps));
         const bool prof = h->prof_on && h->prof_used < h->prof_cap;
         if (prof) HIP_TRY(h, hipEventRecord(h->prof_ev[2 * h->prof_used], st));
         HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, h->w_gate_up[l], w.act, M, 2 * f, d));
         if (prof) HIP_TRY(h, hipEventRecord(h->prof_ev[2 * h->prof_used++ + 1], st));
-        pending = gemm_num_splits(M, d, f);
-        if (int rc = slab_check(h, pending, M)) return rc;
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, h->w_down[l], w.partials, M, d, f));
+        pending = gemm_num_splits(M, d, f, slabs);
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, h->w_down[l], w.partials, M, d, f, slabs));
     }
     HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, M, d, c.rms_eps));
     if (!win) {
@@ -267,29 +273,35 @@ int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, con
         if (rc != DLLM_OK) return rc;
         w.kv_cache = bufs;
     }
-    // the recomputed rows, in order, and where each sequence's rows start
-    std::vector<int32_t> rows, pos;
-    rows.reserve((size_t)B * L); pos.reserve((size_t)B * L);
+    // the recomputed rows, in order, and where each sequence's rows start; the lists are built in pinned
+    // memory (two slots in turn: the copy of the step before may still be waiting for its turn on the stream)
+    const int slot = w.rows_slot;
+    w.rows_slot ^= 1;
+    HIP_TRY(h, hipEventSynchronize(w.rows_copied[slot]));
+    int32_t *rows = w.host_rows[slot], *pos = rows + Mmax;
     SeqRows sr;
     bool any_skip = false;
+    int Ma = 0;
     for (int b = 0; b < B; ++b) {
-        sr.first[b] = (int)rows.size();
+        sr.first[b] = Ma;
         for (int i = 0; i < L; ++i) {
             if (skip && skip[(size_t)b * L + i]) { any_skip = true; continue; }
-            rows.push_back(b * L + i);
-            pos.push_back(i);
+            rows[Ma] = b * L + i;
+            pos[Ma] = i;
+            ++Ma;
         }
-        sr.count[b] = (int)rows.size() - sr.first[b];
+        sr.count[b] = Ma - sr.first[b];
     }
-    const int Ma = (int)rows.size();
     if (any_skip && !(w.cache_valid && w.cache_B == B && w.cache_L == L))
         return fail(h, DLLM_ESTATE, "positions are skipped but no step has filled the cache for this batch shape yet");
     if (Ma == 0) return fail(h, DLLM_EINVAL, "every position is skipped");
-    // pageable source: the runtime stages it before returning, so the vectors may go out of scope
-    HIP_TRY(h, hipMemcpyAsync(w.rows_d, rows.data(), (size_t)Ma * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    HIP_TRY(h, hipMemcpyAsync(w.pos_d, pos.data(), (size_t)Ma * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(w.rows_d, rows, (size_t)Ma * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(w.pos_d, pos, (size_t)Ma * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipEventRecord(w.rows_copied[slot], st));
 
-    HIP_TRY(h, launch_embed(st, tokens, w.rows_d, h->embed, w.x, Ma, d));
+    HIP_TRY(h, launch_embed(st, tokens, w.rows_d, h->embed, w.x, Ma, d, c.vocab, w.bad_token));
+    const int slabs = slab_limit(h, Ma);
+    if (slabs < 1) return fail(h, DLLM_ESTATE, "the split-K workspace does not hold one slab of %d rows", Ma);
     int pending = 0;
     for (int l = 0; l < c.n_layers; ++l) {
         HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->attn_norm[l], w.h, Ma, d, c.rms_eps));
@@ -302,14 +314,12 @@ int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, con
             HIP_TRY(h, launch_scatter_kv(st, w.qkv, w.kv_cache[l], w.rows_d, Ma, d));
             HIP_TRY(h, launch_attention_rows(st, w.qkv, w.kv_cache[l], w.att, B, L, c.n_heads, c.head_dim, sr));
         }
-        pending = gemm_num_splits(Ma, d, d);
-        if (int rc = slab_check(h, pending, Ma)) return rc;
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, Ma, d, d));
+        pending = gemm_num_splits(Ma, d, d, slabs);
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, Ma, d, d, slabs));
         HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->ffn_norm[l], w.h, Ma, d, c.rms_eps));
         HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, h->w_gate_up[l], w.act, Ma, 2 * f, d));
-        pending = gemm_num_splits(Ma, d, f);
-        if (int rc = slab_check(h, pending, Ma)) return rc;
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, h->w_down[l], w.partials, Ma, d, f));
+        pending = gemm_num_splits(Ma, d, f, slabs);
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, h->w_down[l], w.partials, Ma, d, f, slabs));
     }
     HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, Ma, d, c.rms_eps));
     // logits stay indexed by absolute row; the rows of a window are consecutive among the recomputed ones
@@ -327,6 +337,15 @@ int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, con
     h->last_B = B;
     h->last_L = L;
     return DLLM_OK;
+}
+
+// The embedding kernel met a token id outside [0, vocab) (it used a row of zeros instead): clear the
+// flag and report it.  Called after a synchronisation that brought the flag to the host.
+int bad_token_seen(dllm_handle *h)
+{
+    (void)hipMemsetAsync(h->ws.bad_token, 0, sizeof(int32_t), h->stream);
+    return fail(h, DLLM_EINVAL, "a token id outside [0, %d) was passed in `tokens`; the steps that read it used an "
+                                "all-zero embedding, so their results are not meaningful", h->cfg.vocab);
 }
 
 int check_batch(dllm_handle *h, int B, int L)
@@ -487,14 +506,10 @@ int dllm_create(const dllm_config *cfg, const dllm_weights *w, void *hip_stream,
     A(dev_alloc(h, &s.qkv, M * 3 * d));
     A(dev_alloc(h, &s.att, M * d));
     A(dev_alloc(h, &s.act, M * f));
-    // slabs: every split count fits up to 4096 rows; beyond that the planner's own choice (few or no splits once
-    // the row tiles alone fill the chip) decides, sampled every 256 rows; slab_check guards each launch
-    size_t slab_rows = (size_t)kMaxSplits * (M < 4096 ? M : 4096);
-    for (size_t m = 4096; m <= M; m = (m + 256 <= M || m == M) ? m + 256 : M) {
-        const size_t so = (size_t)gemm_num_splits((int)m, (int)d, (int)d), sd = (size_t)gemm_num_splits((int)m, (int)d, (int)f);
-        const size_t need = (so > sd ? so : sd) * m;
-        if (need > slab_rows) slab_rows = need;
-    }
+    // slabs: every split count fits up to 4096 rows, two slabs beyond (once the row tiles alone fill the chip
+    // the planner wants few or no splits); each launch hands the planner the number of slabs that fit
+    size_t slab_rows = (size_t)kGemmMaxSplits * (M < 4096 ? M : 4096);
+    if (2 * M > slab_rows) slab_rows = 2 * M;
     s.partials_cap = slab_rows * d;
     A(dev_alloc(h, &s.partials, s.partials_cap));
     A(dev_alloc(h, &s.rowstats, 3 * gemm_rowstats_max_parts(c.vocab) * M));
@@ -502,16 +517,30 @@ int dllm_create(const dllm_config *cfg, const dllm_weights *w, void *hip_stream,
     A(dev_alloc(h, &s.conf, M));
     A(dev_alloc(h, &s.rope, (size_t)c.max_seq * (c.head_dim / 2)));
     A(dev_alloc(h, &s.prev_pred, M));
-    A(dev_alloc(h, &s.cl_ints, (size_t)4 * c.max_batch));
+    A(dev_alloc(h, &s.cl_ints, (size_t)4 * c.max_batch + 1));
+    if (rc == DLLM_OK) {
+        s.bad_token = s.cl_ints + 4 * c.max_batch;
+        if (hipMemsetAsync(s.cl_ints, 0, ((size_t)4 * c.max_batch + 1) * sizeof(int32_t), h->stream) != hipSuccess)
+            rc = fail(h, DLLM_EHIP, "dllm_create: hipMemsetAsync failed");
+    }
     A(dev_alloc(h, &s.cl_pos, M));
     A(dev_alloc(h, &s.cl_tok, M));
     A(dev_alloc(h, &s.cl_conf, M));
-    if (rc == DLLM_OK && hipHostMalloc(reinterpret_cast<void **>(&s.host_pinned), M + 16 * c.max_batch + 64,
+    const size_t m64 = (M + 63) & ~(size_t)63, ints64 = (((size_t)4 * c.max_batch + 1) * 4 + 63) & ~(size_t)63;
+    if (rc == DLLM_OK && hipHostMalloc(reinterpret_cast<void **>(&s.host_pinned), m64 + ints64 + 5 * M * 4 + 64,
                                        hipHostMallocDefault) != hipSuccess) {
         (void)hipGetLastError();
         rc = fail(h, DLLM_ENOMEM, "dllm_create: pinned host allocation failed");
     }
-    if (rc == DLLM_OK && (hipEventCreate(&h->ev0) != hipSuccess || hipEventCreate(&h->ev1) != hipSuccess))
+    if (rc == DLLM_OK) {
+        s.host_ints = reinterpret_cast<int32_t *>(s.host_pinned + m64);
+        s.host_conf = reinterpret_cast<float *>(s.host_pinned + m64 + ints64);
+        s.host_rows[0] = reinterpret_cast<int32_t *>(s.host_conf + M);
+        s.host_rows[1] = s.host_rows[0] + 2 * M;
+    }
+    if (rc == DLLM_OK && (hipEventCreate(&h->ev0) != hipSuccess || hipEventCreate(&h->ev1) != hipSuccess ||
+                          hipEventCreateWithFlags(&s.rows_copied[0], hipEventDisableTiming) != hipSuccess ||
+                          hipEventCreateWithFlags(&s.rows_copied[1], hipEventDisableTiming) != hipSuccess))
         rc = fail(h, DLLM_EHIP, "dllm_create: hipEventCreate failed");
     if (rc == DLLM_OK && launch_rope_table(h->stream, s.rope, c.max_seq, c.head_dim, c.rope_theta) != hipSuccess)
         rc = fail(h, DLLM_EHIP, "dllm_create: rope table launch failed");
@@ -535,6 +564,8 @@ void dllm_destroy(dllm_handle *h)
     for (hipEvent_t e : h->prof_ev) (void)hipEventDestroy(e);
     if (h->ev0) (void)hipEventDestroy(h->ev0);
     if (h->ev1) (void)hipEventDestroy(h->ev1);
+    for (hipEvent_t e : h->ws.rows_copied)
+        if (e) (void)hipEventDestroy(e);
     delete h;
 }
 
@@ -561,6 +592,16 @@ int dllm_step(dllm_handle *h, int32_t B, int32_t L, int32_t *tokens, uint8_t *ma
         HIP_TRY(h, launch_row_phase(h->stream, h->ws.logits, B, L, h->cfg.vocab, h->cfg.mask_id, mask, args, h->ws.pred,
                                     h->ws.conf));
     HIP_TRY(h, launch_seq_phase(h->stream, B, L, tokens, mask, prev_pred, h->ws.pred, h->ws.conf, args, co));
+    return DLLM_OK;
+}
+
+int dllm_sync_status(dllm_handle *h)
+{
+    if (!h) return fail(nullptr, DLLM_EINVAL, "dllm_sync_status: handle is null");
+    int32_t *flag = h->ws.host_ints + 4 * h->cfg.max_batch;
+    HIP_TRY(h, hipMemcpyAsync(flag, h->ws.bad_token, sizeof(int32_t), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    if (*flag != 0) return bad_token_seen(h);
     return DLLM_OK;
 }
 
@@ -656,7 +697,7 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
     // prev_pred <- -1 (all bytes 0xff)
     HIP_TRY(h, hipMemsetAsync(w.prev_pred, 0xff, (size_t)B * L * sizeof(int32_t), st));
     uint8_t *hmask = w.host_pinned;
-    int32_t *hints = reinterpret_cast<int32_t *>(w.host_pinned + (((size_t)h->cfg.max_batch * h->cfg.max_seq + 63) & ~(size_t)63));
+    int32_t *hints = w.host_ints;
     HIP_TRY(h, hipMemcpyAsync(hmask, mask, (size_t)B * L, hipMemcpyDeviceToHost, st));
     HIP_TRY(h, hipStreamSynchronize(st));
 
@@ -671,7 +712,7 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
     std::vector<dllm_stage_params> sps(B);
     std::vector<int32_t> modes(B, DLLM_CACHE_OFF);
     std::vector<uint8_t> skip((size_t)B * L, 0);
-    std::vector<float> hconf(p->out_of_span_cache ? (size_t)B * L : 0);
+    float *hconf = w.host_conf;
     int steps = 0;
     for (;;) {
         bool live = false;
@@ -721,16 +762,17 @@ int dllm_decode(dllm_handle *h, int32_t B, int32_t L, int32_t gen_start, int32_t
         }
         if (timed) HIP_TRY(h, hipEventRecord(h->ev1, st));
         HIP_TRY(h, hipMemcpyAsync(hmask, mask, (size_t)B * L, hipMemcpyDeviceToHost, st));
-        HIP_TRY(h, hipMemcpyAsync(hints, w.cl_ints, (size_t)4 * mb * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        HIP_TRY(h, hipMemcpyAsync(hints, w.cl_ints, ((size_t)4 * mb + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, st));
         if (any_refresh)  // the confidences decide what is cached for the rest of the stage
-            HIP_TRY(h, hipMemcpyAsync(hconf.data(), w.conf, (size_t)B * L * sizeof(float), hipMemcpyDeviceToHost, st));
+            HIP_TRY(h, hipMemcpyAsync(hconf, w.conf, (size_t)B * L * sizeof(float), hipMemcpyDeviceToHost, st));
         HIP_TRY(h, hipStreamSynchronize(st));
+        if (hints[4 * mb] != 0) return bad_token_seen(h);
         int committed = 0;
         for (int b = 0; b < B; ++b) {
             if (sps[b].stage == DLLM_STAGE_IDLE) continue;
             committed += hints[b];
             ctl[b].observe(hints[mb + b], hints[2 * mb + b], hmask + (size_t)b * L,
-                           any_refresh ? hconf.data() + (size_t)b * L : nullptr);
+                           any_refresh ? hconf + (size_t)b * L : nullptr);
         }
         if (timed) {
             float ms = 0.0f;
@@ -768,7 +810,7 @@ int dllm_decode_low_confidence(dllm_handle *h, int32_t B, int32_t L, int32_t gen
     hipStream_t st = h->stream;
     HIP_TRY(h, hipMemsetAsync(w.prev_pred, 0xff, (size_t)B * L * sizeof(int32_t), st));
     uint8_t *hmask = w.host_pinned;
-    int32_t *hints = reinterpret_cast<int32_t *>(w.host_pinned + (((size_t)h->cfg.max_batch * h->cfg.max_seq + 63) & ~(size_t)63));
+    int32_t *hints = w.host_ints;
     HIP_TRY(h, hipMemcpyAsync(hmask, mask, (size_t)B * L, hipMemcpyDeviceToHost, st));
     HIP_TRY(h, hipStreamSynchronize(st));
 
@@ -805,8 +847,9 @@ int dllm_decode_low_confidence(dllm_handle *h, int32_t B, int32_t L, int32_t gen
             if ((rc = dllm_step(h, B, L, tokens, mask, w.prev_pred, sps.data(), &cl))) return rc;
             if (timed) HIP_TRY(h, hipEventRecord(h->ev1, st));
             HIP_TRY(h, hipMemcpyAsync(hmask, mask, (size_t)B * L, hipMemcpyDeviceToHost, st));
-            HIP_TRY(h, hipMemcpyAsync(hints, w.cl_ints, (size_t)4 * mb * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+            HIP_TRY(h, hipMemcpyAsync(hints, w.cl_ints, ((size_t)4 * mb + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, st));
             HIP_TRY(h, hipStreamSynchronize(st));
+            if (hints[4 * mb] != 0) return bad_token_seen(h);
             if (timed) {
                 int committed = 0;
                 for (int b = 0; b < B; ++b)
@@ -851,6 +894,19 @@ int dllm_profile_end(dllm_handle *h, float *total_ms, int32_t *launches)
     }
     *total_ms = tot;
     *launches = h->prof_used;
+    return DLLM_OK;
+}
+
+void dllm_debug_reload_env(void) { gemm_reload_env(); }
+
+int dllm_debug_gemm_plan(int32_t epilogue, int32_t M, int32_t N, int32_t K, int32_t split_limit, int32_t *out8)
+{
+    if (!out8) return fail(nullptr, DLLM_EINVAL, "dllm_debug_gemm_plan: out8 is null");
+    if (epilogue < 0 || epilogue > 5 || M < 1 || N < 1 || K < 8 || K % 8)
+        return fail(nullptr, DLLM_EINVAL, "dllm_debug_gemm_plan: epilogue in [0, 5], M, N >= 1, K a positive multiple of 8");
+    const GemmPlanInfo p = gemm_plan_info(epilogue, M, N, K, split_limit);
+    const int32_t v[8] = {p.bm, p.bn, p.bk, p.stages, p.waves_m, p.waves_n, p.splits, p.async_copy};
+    memcpy(out8, v, sizeof v);
     return DLLM_OK;
 }
 
@@ -902,8 +958,8 @@ int dllm_op_add_rmsnorm(void *hip_stream, float *x, const float *partials, int32
                         void *hout, int32_t M, int32_t d, float eps)
 {
     if (!x || !gain || !hout || (n_partials > 0 && !partials)) return fail(nullptr, DLLM_EINVAL, "dllm_op_add_rmsnorm: null argument");
-    if (M < 1 || d < 4 || d % 4 || n_partials < 0 || n_partials > kMaxSplits)
-        return fail(nullptr, DLLM_EINVAL, "dllm_op_add_rmsnorm: need M >= 1, d a positive multiple of 4, 0 <= n_partials <= %d", kMaxSplits);
+    if (M < 1 || d < 4 || d % 4 || n_partials < 0 || n_partials > kGemmMaxSplits)
+        return fail(nullptr, DLLM_EINVAL, "dllm_op_add_rmsnorm: need M >= 1, d a positive multiple of 4, 0 <= n_partials <= %d", kGemmMaxSplits);
     if (!aligned16(x) || !aligned16(gain) || !aligned16(hout) || !aligned16(partials)) return fail(nullptr, DLLM_EINVAL, "dllm_op_add_rmsnorm: pointers must be 16-byte aligned");
     HIP_TRY(nullptr, launch_add_rmsnorm(static_cast<hipStream_t>(hip_stream), x, partials, n_partials, gain, hout, M, d, eps));
     return DLLM_OK;

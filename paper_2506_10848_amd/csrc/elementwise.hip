@@ -9,14 +9,22 @@ namespace {
 
 constexpr int kThreads = 256;
 
-// x[r][:] = float(E[tokens[r]][:]); d % 8 == 0.
+// x[r][:] = float(E[tokens[r]][:]); d % 8 == 0.  An id outside [0, vocab) is never used as an index:
+// its row becomes zeros and *bad_token is set to 1 (the host reports it at its next synchronisation).
 __global__ __launch_bounds__(kThreads) void embed_kernel(const int32_t *__restrict__ tokens,
                                                          const int32_t *__restrict__ rows,
-                                                         const uint16_t *__restrict__ E, float *__restrict__ x, int d)
+                                                         const uint16_t *__restrict__ E, float *__restrict__ x, int d,
+                                                         int vocab, int32_t *__restrict__ bad_token)
 {
     const int r = blockIdx.x;
-    const uint4 *src = reinterpret_cast<const uint4 *>(E + (size_t)tokens[rows ? rows[r] : r] * d);
+    const int tok = tokens[rows ? rows[r] : r];
     float4 *dst = reinterpret_cast<float4 *>(x + (size_t)r * d);
+    if ((unsigned)tok >= (unsigned)vocab) {  // uniform over the workgroup
+        for (int c = threadIdx.x; c < d / 4; c += kThreads) dst[c] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (threadIdx.x == 0 && bad_token) *bad_token = 1;
+        return;
+    }
+    const uint4 *src = reinterpret_cast<const uint4 *>(E + (size_t)tok * d);
     for (int c = threadIdx.x; c < d / 8; c += kThreads) {
         const uint4 q = src[c];
         dst[2 * c] = make_float4(bf16_lo(q.x), bf16_hi(q.x), bf16_lo(q.y), bf16_hi(q.y));
@@ -137,9 +145,10 @@ __global__ __launch_bounds__(kThreads) void rope_kernel(uint16_t *__restrict__ q
 }  // namespace
 
 hipError_t launch_embed(hipStream_t stream, const int32_t *tokens, const int32_t *rows, const void *embed, float *x,
-                        int M, int d)
+                        int M, int d, int vocab, int32_t *bad_token)
 {
-    hipLaunchKernelGGL(embed_kernel, dim3(M), dim3(kThreads), 0, stream, tokens, rows, (const uint16_t *)embed, x, d);
+    hipLaunchKernelGGL(embed_kernel, dim3(M), dim3(kThreads), 0, stream, tokens, rows, (const uint16_t *)embed, x, d,
+                       vocab, bad_token);
     return hipGetLastError();
 }
 

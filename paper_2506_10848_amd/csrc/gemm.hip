@@ -53,6 +53,10 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <map>
+#include <mutex>
+#include <tuple>
+
 #include "internal.h"
 
 namespace dllm {
@@ -616,10 +620,43 @@ struct Plan {
     bool fast;  // gemm_il_kernel
 };
 
+// Test and tuning hooks from the environment, read once (and again by gemm_reload_env): DLLM_GEMM_FALLBACK
+// forces the register-staged kernel, DLLM_NO_FUSED_ROPE the separate rotary kernel, DLLM_GEMM_CFG a tile
+// shape for every product, DLLM_GEMM_CFG_E<epilogue> for one epilogue, DLLM_GEMM_SPLITS a split count.
+constexpr int kNumEpi = 6;
+struct EnvHooks {
+    bool loaded = false;
+    int fallback = 0, no_fused_rope = 0, cfg_all = -1, cfg_epi[kNumEpi] = {-1, -1, -1, -1, -1, -1}, splits = -1;
+};
+std::mutex g_plan_mutex;  // guards g_env and g_plans
+EnvHooks g_env;
+std::map<std::tuple<int, int, int, int, int>, Plan> g_plans;  // (epilogue, M, N, K, split limit) -> plan
+
 int env_int(const char *name, int dflt)
 {
     const char *s = getenv(name);
     return s ? atoi(s) : dflt;
+}
+
+void load_env_locked()
+{
+    g_env.fallback = env_int("DLLM_GEMM_FALLBACK", 0);
+    g_env.no_fused_rope = env_int("DLLM_NO_FUSED_ROPE", 0);
+    g_env.cfg_all = env_int("DLLM_GEMM_CFG", -1);
+    for (int e = 0; e < kNumEpi; ++e) {
+        char name[32];
+        snprintf(name, sizeof name, "DLLM_GEMM_CFG_E%d", e);
+        g_env.cfg_epi[e] = env_int(name, -1);
+    }
+    g_env.splits = env_int("DLLM_GEMM_SPLITS", -1);
+    g_env.loaded = true;
+}
+
+EnvHooks env_hooks()
+{
+    std::lock_guard<std::mutex> lock(g_plan_mutex);
+    if (!g_env.loaded) load_env_locked();
+    return g_env;
 }
 
 // epi: a GemmEpilogue value or one of the rotary epilogues
@@ -636,19 +673,15 @@ bool cfg_allows(int c, int epi, bool fast)
 
 // Lowest modelled time: rounds of workgroups over the CUs, each round costing
 // the K-steps of one tile plus its epilogue, plus the traffic of the fp32 slabs.
-Plan make_plan(int epi, int M, int N, int K)
+Plan search_plan(const EnvHooks &env, int epi, int M, int N, int K, int split_limit)
 {
     const int n_out = epi == kEpiSwiglu ? N / 2 : N;
     // the asynchronous-copy kernel needs whole K-steps and 32-bit byte offsets
-    const bool fast = (K % 64 == 0) && ((double)M * K * 2 < 4.0e9) && ((double)N * K * 2 < 4.0e9) &&
-                      env_int("DLLM_GEMM_FALLBACK", 0) == 0;
-    // test and tuning hooks: DLLM_GEMM_CFG forces a tile shape for every product, DLLM_GEMM_CFG_E<epilogue> for one epilogue
-    char per_epi[32];
-    snprintf(per_epi, sizeof per_epi, "DLLM_GEMM_CFG_E%d", epi);
-    const int fc = env_int(per_epi, env_int("DLLM_GEMM_CFG", -1)), fs = env_int("DLLM_GEMM_SPLITS", -1);
+    const bool fast = (K % 64 == 0) && ((double)M * K * 2 < 4.0e9) && ((double)N * K * 2 < 4.0e9) && env.fallback == 0;
+    const int fc = (epi >= 0 && epi < kNumEpi && env.cfg_epi[epi] >= 0) ? env.cfg_epi[epi] : env.cfg_all, fs = env.splits;
     Plan best{4, 1, fast};
     double best_cost = 1e300;
-    const int max_splits = epi == kEpiPartial ? 8 : 1;
+    const int max_splits = epi == kEpiPartial ? (split_limit < 1 ? 1 : split_limit > kGemmMaxSplits ? kGemmMaxSplits : split_limit) : 1;
     for (int c = 0; c < kNumCfg; ++c) {
         if (!cfg_allows(c, epi, fast) || (fc >= 0 && fc < kNumCfg && cfg_allows(fc, epi, fast) && c != fc)) continue;
         // a single row of 256x256 tiles that only streams W (the vocabulary projection of one window) measures
@@ -683,6 +716,19 @@ Plan make_plan(int epi, int M, int N, int K)
     return best;
 }
 
+// The plan of a product is searched once per (epilogue, shape, split limit) and kept.
+Plan make_plan(int epi, int M, int N, int K, int split_limit = kGemmMaxSplits)
+{
+    const auto key = std::make_tuple(epi, M, N, K, split_limit);
+    std::lock_guard<std::mutex> lock(g_plan_mutex);
+    if (!g_env.loaded) load_env_locked();
+    auto it = g_plans.find(key);
+    if (it != g_plans.end()) return it->second;
+    const Plan p = search_plan(g_env, epi, M, N, K, split_limit);
+    g_plans.emplace(key, p);
+    return p;
+}
+
 template <int BM, int BN, int WM, int WN, int BK, int NST, int EPI>
 hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *W, void *C, int M, int N, int K,
                       int splits, RopeArgs rope = RopeArgs{nullptr, nullptr, {1}, {0}})
@@ -695,13 +741,10 @@ hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *
     if (fast) {
         const size_t lds = (size_t)NST * (BM + BN) * BK * 2;
         auto kern = gemm_il_kernel<BM, BN, WM, WN, BK, NST, EPI>;
-        static bool attr_done = false;
-        if (!attr_done) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        // once per kernel, whichever thread comes first (initialisation of a local static is thread-safe)
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (attr != hipSuccess) return attr;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, (const uint16_t *)A, (const uint16_t *)W, C, M, N, K, kps,
                            num_m, num_n, rope);
     } else if constexpr (BM * BN > 256 * 128) {
@@ -709,13 +752,9 @@ hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *
     } else {
         const size_t lds = (size_t)2 * (BM + BN) * 128;
         auto kern = gemm_reg_kernel<BM, BN, WM, WN, EPI>;
-        static bool attr_done = false;
-        if (!attr_done) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (attr != hipSuccess) return attr;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, (const uint16_t *)A, (const uint16_t *)W, C, M, N, K, kps,
                            num_m, num_n, rope);
     }
@@ -742,13 +781,28 @@ hipError_t dispatch(hipStream_t stream, Plan p, const void *A, const void *W, vo
 
 }  // namespace
 
-int gemm_num_splits(int M, int N, int K) { return make_plan(kEpiPartial, M, N, K).splits; }
+int gemm_num_splits(int M, int N, int K, int split_limit) { return make_plan(kEpiPartial, M, N, K, split_limit).splits; }
+
+GemmPlanInfo gemm_plan_info(int epi, int M, int N, int K, int split_limit)
+{
+    const Plan p = make_plan(epi, M, N, K, split_limit);
+    const TileCfg &t = kCfg[p.cfg];
+    return GemmPlanInfo{t.bm, t.bn, p.fast ? t.bk : 64, p.fast ? t.nst : 2, 4 / t.wn, t.wn, p.splits, p.fast ? 1 : 0};
+}
+
+void gemm_reload_env()
+{
+    std::lock_guard<std::mutex> lock(g_plan_mutex);
+    load_env_locked();
+    g_plans.clear();
+}
 
 bool gemm_qkv_rope_supported(int M, int d, int dh)
 {
     // pairs (c, c + dh/2) in groups of 16 inside one head; the q/k boundary on a head edge; asynchronous-copy kernel
+    const EnvHooks env = env_hooks();
     return (dh == 64 || dh == 128) && d % dh == 0 && d % 64 == 0 && (double)M * d * 2 < 4.0e9 &&
-           (double)3 * d * d * 2 < 4.0e9 && env_int("DLLM_GEMM_FALLBACK", 0) == 0 && env_int("DLLM_NO_FUSED_ROPE", 0) == 0;
+           (double)3 * d * d * 2 < 4.0e9 && env.fallback == 0 && env.no_fused_rope == 0;
 }
 
 hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
@@ -776,9 +830,9 @@ hipError_t launch_gemm_rowstats(hipStream_t stream, const void *A, const void *W
 }
 
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
-                       int K)
+                       int K, int split_limit)
 {
-    const Plan p = make_plan(epi, M, N, K);
+    const Plan p = make_plan(epi, M, N, K, split_limit);
     switch (epi) {
     case kEpiBf16: return dispatch<kEpiBf16>(stream, p, A, W, C, M, N, K);
     case kEpiSwiglu: return dispatch<kEpiSwiglu>(stream, p, A, W, C, M, N, K);

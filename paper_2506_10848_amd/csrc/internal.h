@@ -37,9 +37,10 @@ hipError_t launch_rowstats_merge(hipStream_t stream, const float *stats, int par
                                  const uint8_t *mask, const SelectArgs &args, int32_t *pred, float *conf);
 
 // ---- forward pass -------------------------------------------------------------
-// rows (nullable): x[r] is the embedding of tokens[rows[r]] instead of tokens[r]
+// rows (nullable): x[r] is the embedding of tokens[rows[r]] instead of tokens[r].  A token id outside
+// [0, vocab) gives a row of zeros and sets *bad_token (device int32, nullable) to 1.
 hipError_t launch_embed(hipStream_t stream, const int32_t *tokens, const int32_t *rows, const void *embed, float *x,
-                        int M, int d);
+                        int M, int d, int vocab, int32_t *bad_token);
 // dst[rows[r]][d .. 3d) = src[r][d .. 3d): the k and v thirds of recomputed rows go to their cache rows
 hipError_t launch_scatter_kv(hipStream_t stream, const void *src, void *dst, const int32_t *rows, int n_rows, int d);
 hipError_t launch_add_rmsnorm(hipStream_t stream, float *x, const float *partials, int n_partials, const void *gain,
@@ -61,8 +62,21 @@ enum GemmEpilogue {
     kEpiSwiglu = 1,   // W = [gate | up] rows; C bf16 [M][N/2] = silu(gate) * up
     kEpiPartial = 2,  // C fp32 [splits][M][N], one slab per K split
 };
-// How many K splits launch_gemm will use for a kEpiPartial problem (>= 1).
-int gemm_num_splits(int M, int N, int K);
+// How many K splits launch_gemm will use for a kEpiPartial problem: between 1 and min(split_limit,
+// kGemmMaxSplits).  The caller derives split_limit from the slab space it has and passes the same value
+// to launch_gemm, so a plan never asks for more slabs than exist.
+constexpr int kGemmMaxSplits = 8;
+int gemm_num_splits(int M, int N, int K, int split_limit = kGemmMaxSplits);
+// What launch_gemm (epi = a GemmEpilogue), launch_gemm_qkv_rope (epi = 3 for head_dim 64, 4 for 128) or
+// launch_gemm_rowstats (epi = 5) will launch for a shape: tile, K depth of a stage, ring stages, wave grid,
+// K splits, and whether it is the asynchronous-copy kernel (1) or the register-staged one (0).
+struct GemmPlanInfo {
+    int bm, bn, bk, stages, waves_m, waves_n, splits, async_copy;
+};
+GemmPlanInfo gemm_plan_info(int epi, int M, int N, int K, int split_limit = kGemmMaxSplits);
+// Reads the DLLM_GEMM_* / DLLM_NO_FUSED_ROPE environment hooks again and forgets every cached plan
+// (they are otherwise read once per process); for tests that switch kernels between calls.
+void gemm_reload_env();
 // QKV projection with the rotary embedding of the q and k thirds fused into the
 // epilogue: C bf16 [M][3d] = A[M][d] * W[3d][d]^T, rows are positions row % L.
 bool gemm_qkv_rope_supported(int M, int d, int dh);
@@ -71,7 +85,7 @@ hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W
                                 const float2 *table, int L, const int32_t *pos = nullptr);
 // C = A[M][K] * W[N][K]^T.  For kEpiSwiglu N counts gate + up rows.
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
-                       int K);
+                       int K, int split_limit = kGemmMaxSplits);
 // The same product with the greedy decode fused in: no C; per row and per column slice (a wave's
 // share of a tile, *parts of them) the maximum of the bf16-rounded values, the sum of
 // exp(x - max) and the lowest column holding the maximum, column mask_id left out.

@@ -340,13 +340,10 @@ hipError_t launch_seq_phase(hipStream_t stream, int B, int L, int32_t *tokens, u
                             const int32_t *pred, const float *conf, const SelectArgs &args, const CommitOut &out)
 {
     const size_t lds = (size_t)L * 9 + 16;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(seq_phase_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 9 + 16);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once, whichever thread comes first (initialisation of a local static is thread-safe)
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(seq_phase_kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 9 + 16);
+    if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(seq_phase_kernel, dim3(B), dim3(kSeqThreads), lds, stream, L, tokens, mask, prev_pred, pred,
                        conf, args, out);
     return hipGetLastError();

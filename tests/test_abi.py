@@ -97,3 +97,23 @@ def test_select_validates_before_launching():
     assert rc == b.EINVAL
     rc = lib.dllm_select(None, fake, 1, 8, 64, 64, fake, fake, fake, sp, fake, fake, C.byref(cl))
     assert rc == b.EINVAL and "mask_id" in lib.dllm_last_error(None).decode()
+
+
+def test_split_count_never_exceeds_the_slabs_that_fit():
+    """The O and down projections write one fp32 slab per K split into a workspace sized at create;
+    each launch tells the planner how many slabs of its row count fit.  Sweep of row counts (cached
+    steps recompute arbitrary subsets) for a narrow and a wide model: the plan obeys the limit, also
+    between the multiples of the tile heights."""
+    b.reload_env()
+    for d, f in [(256, 688 + 16), (4096, 12288)]:
+        for rows in list(range(4090, 4110)) + list(range(4097, 12289, 97)) + [12288]:
+            for limit in (1, 2, 8):
+                for N, K in [(d, d), (d, f)]:
+                    if K % 64:
+                        continue
+                    p = b.gemm_plan(2, rows, N, K, limit)
+                    assert 1 <= p["splits"] <= limit
+    # no limit given: at most 8
+    assert b.gemm_plan(2, 512, 4096, 12288)["splits"] <= 8
+    # other epilogues never split
+    assert b.gemm_plan(1, 512, 24576, 4096)["splits"] == 1 and b.gemm_plan(5, 256, 126464, 4096)["splits"] == 1

@@ -11,8 +11,6 @@ its own magnitude (it is the rounding noise of the activations summed over a
 K-term dot product), so "relative" is taken against the largest magnitude of
 the tensor and of each row, and, per row, at the arg max logit against itself
 (the entry the selector's prediction and confidence hang on)."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -28,6 +26,7 @@ DEV = "cuda"
 def binding():
     from paper_2506_10848_amd import binding as b
     b.lib()
+    b.reload_env()          # the environment switches a test may have set (or a finished test has restored)
     return b
 
 
@@ -200,11 +199,10 @@ def test_attention_full_size_sampled():
 
 # ---- whole forward ------------------------------------------------------------
 
-def logits_close(got, ref, bar=2e-2, rowwise=True):
+def logits_close(got, ref, bar=2e-2, row_bar=None):
     err = np.abs(got - ref)
     assert err.max() / np.abs(ref).max() <= bar                                       # normwise, per tensor
-    if rowwise:
-        assert (err.max(axis=1) / np.abs(ref).max(axis=1)).max() <= bar               # normwise, per row
+    assert (err.max(axis=1) / np.abs(ref).max(axis=1)).max() <= (bar if row_bar is None else row_bar)   # per row
     am = ref.argmax(axis=1)
     r = np.arange(ref.shape[0])
     assert (err[r, am] / np.abs(ref[r, am])).max() <= bar                             # the arg max logit itself
@@ -272,11 +270,20 @@ def test_forward_llada8b_shape_two_layers_sampled_rows():
     logits_close(got, ref)
 
 
-@pytest.mark.skipif(os.environ.get("DLLM_RUN_SLOW") != "1",
-                    reason="the oracle needs minutes of CPU time for all 32 layers; set DLLM_RUN_SLOW=1")
 def test_forward_llada8b_all_layers_sampled_rows():
-    """The benchmark's own model (32 layers) against the oracle on sampled rows.
-    Weights are drawn on the GPU and copied to the host for the oracle."""
+    """The benchmark's own model (32 layers) against the oracle on sampled rows (about a minute of
+    host time for the oracle).  Weights are drawn on the GPU and copied to the host for the oracle.
+
+    Bars.  Per tensor, at every row's arg max logit, and for the rms error over rms logit: the stated
+    2e-2.  Per row (largest error of a row against that row's largest magnitude): 2.5e-2.  Where that
+    comes from: a bf16-activation pipeline measured against an oracle that never rounds carries at least
+    five roundings of activations per layer (norm output, qkv, attention output, norm output, SwiGLU
+    output), each with relative rms error 2^-9 / sqrt(3); over 32 layers that alone is
+    sqrt(160) * 2^-9 / sqrt(3) = 1.43e-2 of the hidden state's norm, hence of a row of logits' rms; the
+    rounded attention probabilities and the errors that earlier layers hand on bring the measured rms
+    figure to 1.9e-2.  Error and logit are both near-Gaussian over the 126464 columns of a row, so a
+    row's max-error over max-logit is that rms figure times the ratio of two extreme-value draws,
+    which spreads by +-25 % from row to row: 2e-2 * 1.25 bounds every row."""
     b = binding()
     cfg = synth.CONFIGS["llada8b"]
     w = synth.make_weights(cfg, device=DEV)
@@ -290,11 +297,45 @@ def test_forward_llada8b_all_layers_sampled_rows():
     err = np.abs(got - ref)
     print("32-layer logits: normwise", err.max() / np.abs(ref).max(), "row-wise",
           (err.max(axis=1) / np.abs(ref).max(axis=1)).max(), "rms ratio", np.sqrt((err ** 2).mean() / (ref ** 2).mean()))
-    # 5 bf16 roundings of activations per layer (norm output, qkv, attention output, norm output, SwiGLU
-    # output), each 2^-9 / sqrt(3) relative, add up to ~1.4e-2 rms over 32 layers against an oracle that
-    # never rounds: the stated 2e-2 bar is held per tensor and at each row's arg max logit, not per row.
-    logits_close(got, ref, rowwise=False)
+    logits_close(got, ref, row_bar=2.5e-2)
+    assert np.sqrt((err ** 2).mean() / (ref ** 2).mean()) <= 2e-2
     m.close()
+
+
+def test_forward_long_batch_shape_one_layer_sampled_rows():
+    """B = 8, L = 1536 at full LLaDA-8B widths and vocabulary (M = 12288 rows: the 256 x 256 tile, the
+    grouped tile order over 48 row tiles, attention without the in-workgroup key split), one of the 32
+    layers.  The oracle side is composed here from the oracle's operators on a sample: keys and values
+    for every position of two of the eight sequences, everything after attention for six query rows."""
+    b = binding()
+    cfg = dict(synth.CONFIGS["llada8b_long"], n_layers=1)
+    mc = synth.model_config(cfg)
+    w = synth.make_weights(cfg, device=DEV)
+    tokens, _, _ = synth.make_state(cfg, device=DEV)
+    B, L = tokens.shape
+    d, H, dh, f = mc["d_model"], mc["n_heads"], mc["head_dim"], mc["d_ffn"]
+    m = b.Model(mc, w, B, L)
+    sample = {0: [0, 700, 1535], 7: [1, 512, 1300]}                   # sequence -> positions
+    rows = np.array([q * L + i for q, ps in sample.items() for i in ps])
+    got = f64(m.forward(tokens)[torch.as_tensor(rows, device=DEV)])
+    torch.cuda.synchronize()
+    m.close()
+    wb = weights_bits(w)
+    tok = tokens.cpu().numpy()
+    eps, theta = mc["rms_eps"], mc["rope_theta"]
+    ref = []
+    for q, ps in sample.items():
+        x = oracle.bf16_to_f64(wb["embed"][tok[q]])                                    # [L, d]
+        qkv = oracle.linear(oracle.rmsnorm(x, wb["attn_norm"][0], eps), wb["wqkv"][0])   # [L, 3d]
+        pos = np.arange(L, dtype=np.int32)
+        qh = oracle.rope(qkv[:, :d].reshape(L, H, dh), pos, theta)
+        kh = oracle.rope(qkv[:, d:2 * d].reshape(L, H, dh), pos, theta)
+        att = oracle.attention(qh, kh, qkv[:, 2 * d:].reshape(L, H, dh)).reshape(L, d)[ps]
+        xs = x[ps] + oracle.linear(att, wb["wo"][0])
+        gu = oracle.linear(oracle.rmsnorm(xs, wb["ffn_norm"][0], eps), wb["w_gate_up"][0])
+        xs = xs + oracle.linear(oracle.swiglu(gu[:, :f], gu[:, f:]), wb["w_down"][0])
+        ref.append(oracle.linear(oracle.rmsnorm(xs, wb["final_norm"], eps), wb["lm_head"]))
+    logits_close(got, np.concatenate(ref))
 
 
 # ---- out-of-span caching: the forward that reuses cached keys/values ---------------

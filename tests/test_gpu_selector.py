@@ -21,6 +21,7 @@ TIE_RTOL = 2e-5           # decisions closer than this to a boundary are not com
 def binding():
     from paper_2506_10848_amd import binding as b
     b.lib()
+    b.reload_env()          # the environment switches a test may have set (or a finished test has restored)
     return b
 
 
@@ -240,3 +241,73 @@ def test_error_paths_reach_the_caller():
         assert ei.value.code == code, kw
     torch.cuda.synchronize()
     assert int(mask.sum()) == 7                     # only the one good call committed anything
+
+
+@pytest.mark.parametrize("workload", ["selector", "selector_peaked"])
+def test_full_size_selector_workload_every_masked_row(workload):
+    """The selector workload at its full size, 16 x 2048 x 126464 bf16 logits (8.3 GB, generated on the
+    GPU), in the launch configuration the benchmark times: slow stage over whole sequences, then the fast
+    stage over the first half of every sequence.  Every masked row of the windows goes through the oracle's
+    row phase (logits copied to the host one sequence at a time): predictions bit-exact, confidences to
+    the 1e-3 bar (and 2e-5 in fact); the 16 commit lists, e_cand, first_masked and the state after the
+    transition against the oracle's selection rule on the oracle's confidences.  `selector` (+U(2,8)
+    peaks) never reaches a threshold: arg max / top-k / empty-e_cand paths; `selector_peaked`
+    (+U(8,18)) crosses both thresholds and the convergence gate."""
+    b = binding()
+    dev = "cuda"
+    cfg = synth.CONFIGS[workload]
+    B, L, V, mask_id = cfg["batch"], cfg["seq"], cfg["vocab"], cfg["mask_id"]
+    logits, mask, planted, agree, other = synth.make_selector_inputs(cfg, dev)
+    h_mask = mask.cpu().numpy()
+    # the oracle's row phase over every masked row, one sequence of logits on the host at a time
+    o_pred = np.full((B, L), -1, np.int32); o_conf = np.zeros((B, L), np.float32)
+    for q in range(B):
+        o_pred[q], o_conf[q] = oracle.row_phase(bits(logits[q]), mask_id, h_mask[q])
+    # previous prediction: the current arg max on the seeded 70 %, another seeded id elsewhere
+    pred_t = torch.from_numpy(o_pred)
+    oth = other.cpu()
+    prev = torch.where(agree.cpu(), pred_t, torch.where(oth == pred_t, (oth + 1) % (V - 1), oth)).to(torch.int32)
+    tokens = torch.full((B, L), mask_id, dtype=torch.int32)
+    tokens[mask.cpu() == 0] = 5
+    n_amb = 0
+    for stage, lo, hi, k, conv in [(sf.SLOW, 0, L - 1, 1, 1), (sf.FAST, 0, L // 2 - 1, 1, 1), (sf.FAST, 7, L - 9, 3, 0)]:
+        sps = [sf.StageParams(stage, lo, hi, k, 0.1, 0.9, conv, 0, L) for _ in range(B)]
+        g_tok, g_mask, g_prev = tokens.to(dev), mask.clone(), prev.to(dev)
+        pred = torch.full((B, L), -7, dtype=torch.int32, device=dev)
+        conf = torch.full((B, L), -7.0, dtype=torch.float32, device=dev)
+        out = b.CommitList(B, L)
+        csp = [b.stage_params(s.stage, s.s_cycle, s.e_cycle, s.top_k, s.tau_min_conf, s.tau_high_conf, s.conv_mode,
+                              s.gen_start, s.gen_end) for s in sps]
+        b.select(logits, g_tok, g_mask, g_prev, csp, mask_id, pred, conf, out)
+        torch.cuda.synchronize()
+        got = out.to_host()
+        g_pred, g_conf = pred.cpu().numpy(), conf.cpu().numpy()
+        act = np.stack([sf.active_rows(sps[q], h_mask[q]) for q in range(B)]).astype(bool)
+        assert act.sum() > 4000
+        assert np.array_equal(g_pred[act], o_pred[act])
+        assert np.all(g_pred[~act] == -7) and np.all(g_conf[~act] == -7.0)        # other rows never touched
+        rel = np.abs(g_conf[act].astype(np.float64) - o_conf[act]) / o_conf[act]
+        assert rel.max() <= CONF_RTOL and rel.max() <= 2e-5
+        g_tok, g_mask, g_prev = g_tok.cpu().numpy(), g_mask.cpu().numpy(), g_prev.cpu().numpy()
+        n_multi = 0
+        for q in range(B):
+            commit, e_cand, first = sf.select(sps[q], h_mask[q], o_pred[q], o_conf[q], prev[q].numpy())
+            g_pos, g_toks, g_cfs, g_e, g_first, g_left = got[q]
+            assert g_first == first
+            if ambiguous(sps[q], h_mask[q], o_conf[q]):
+                n_amb += 1
+                assert all(lo <= i <= hi and h_mask[q, i] for i in g_pos) and g_pos == sorted(g_pos)
+                continue
+            assert g_pos == commit and g_e == e_cand and g_left == int(h_mask[q].sum()) - len(commit)
+            assert g_toks == [int(o_pred[q, i]) for i in commit]
+            want_tok = tokens[q].numpy().copy(); want_tok[commit] = o_pred[q][commit]
+            want_mask = h_mask[q].copy(); want_mask[commit] = 0
+            want_prev = prev[q].numpy().copy(); want_prev[act[q]] = o_pred[q][act[q]]
+            assert np.array_equal(g_tok[q], want_tok) and np.array_equal(g_mask[q], want_mask)
+            assert np.array_equal(g_prev[q], want_prev)
+            n_multi += len(commit) > 1
+        if workload == "selector_peaked" and stage == sf.FAST:
+            assert n_multi >= B - 2                    # the threshold path really fired
+        if workload == "selector":
+            assert all(got[q][3] == -1 for q in range(B))     # nothing exceeds tau_min: e_cand is empty
+    assert n_amb <= 3
