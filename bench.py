@@ -32,6 +32,70 @@ def step_flops(cfg, B, L, vocab_rows):
     return 2.0 * M * nl * (4 * d * d + 3 * d * f) + 2.0 * vocab_rows * d * V + 4.0 * nl * B * L * L * d
 
 
+def gemm_kernel_name(b, epi, M, N, K, what):
+    p = b.gemm_plan(epi, M, N, K)
+    kern = "gemm_il_kernel" if p["async_copy"] else "gemm_reg_kernel"
+    return (f"{kern}<{p['bm']}x{p['bn']} tile, {p['waves_m']}x{p['waves_n']} waves, BK {p['bk']}, {p['stages']} stages, "
+            f"{p['splits']} K split(s), {what}>")
+
+
+def long_batch_extra(b, synth, torch, weights, mc):
+    """B = 8, L = 512 + 1024 on the same LLaDA-8B-shaped weights: one timed step (slow stage over the whole
+    generated region) and a SlowFast decode capped at a stated number of steps with thresholds at quantiles
+    of the first step's confidences, reporting per-stage step time and tokens committed per step."""
+    cfg = synth.CONFIGS["llada8b_long"]
+    B, P, G = cfg["batch"], cfg["prompt"], cfg["gen"]
+    L = P + G
+    tokens0, mask0, prev0 = synth.make_state(cfg, device="cuda")
+    model = b.Model(mc, weights, B, L)
+    out = b.CommitList(B, L)
+    sps = [b.stage_params(b.STAGE_SLOW, P, L - 1, 1, 0.1, 0.9, 1, P, L) for _ in range(B)]
+    tokens, mask, prev = tokens0.clone(), mask0.clone(), prev0.clone()
+    model.step(tokens, mask, prev, sps, out)                      # warm-up
+    n = 3
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    torch.cuda.synchronize()
+    evs[0].record()
+    for i in range(n):
+        model.step(tokens, mask, prev, sps, out)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    step_ms = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(n))[n // 2]
+    flops = step_flops(mc, B, L, vocab_rows=B * G)
+    conf0 = model.debug_rows(B * L)[1].view(B, L)[mask.bool()].float()
+    tau_min_q, tau_high_q = float(conf0.quantile(0.5)), float(conf0.quantile(0.9))
+    cap = 24
+    tokens, mask = tokens0.clone(), mask0.clone()
+    dp = b.DecodeParams(cap, 8, 2, 1, 1, 0, 1.0, tau_min_q, tau_high_q)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    steps, st = model.decode(tokens, mask, P, dp, stats_capacity=cap)
+    t_dec = time.perf_counter() - t0
+    committed = B * G - int(mask.sum())
+    slow = [s for s in st if s[0] > 0 and s[1] == 0]
+    fast = [s for s in st if s[1] > 0 and s[0] == 0]
+    mixed = [s for s in st if s[0] > 0 and s[1] > 0]
+    mean = lambda xs: sum(xs) / max(len(xs), 1)
+    res = {"workload": f"llada8b_long: batch {B}, {P} prompt + {G} masked (L={L}), same weights",
+           "step_ms_median_of_3": step_ms, "tokens_per_s": B * L / (step_ms * 1e-3), "step_tflops": flops / 1e12,
+           "step_mfma_frac": flops / (step_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+           "gate_up_kernel": gemm_kernel_name(b, 1, B * L, 2 * mc["d_ffn"], mc["d_model"], "SwiGLU"),
+           "decode_capped": {
+               "max_steps": cap, "steps": steps, "seconds": t_dec, "tokens_committed": committed,
+               "committed_tokens_per_s": committed / t_dec,
+               "slow_only_steps": len(slow), "fast_only_steps": len(fast), "mixed_steps": len(mixed),
+               "slow_step_ms": mean([s[4] for s in slow]), "fast_step_ms": mean([s[4] for s in fast]),
+               "mixed_step_ms": mean([s[4] for s in mixed]),
+               "tokens_per_slow_step": mean([s[3] for s in slow]), "tokens_per_fast_step": mean([s[3] for s in fast]),
+               "tokens_per_mixed_step": mean([s[3] for s in mixed]),
+               "params": f"N capped at {cap} steps; tau_min = median ({tau_min_q:.3e}), tau_high = 90th percentile "
+                         f"({tau_high_q:.3e}) of the first step's confidences, K_max 8, W_hist 2, sigma2 1.0, "
+                         "k_slow=k_fast=1, conv_mode 0; a step is 'slow only' / 'fast only' / 'mixed' by the stages "
+                         "of the 8 sequences during it"}}
+    model.close()
+    return res
+
+
 def to_bits(t):
     import torch
     return t.detach().cpu().contiguous().view(torch.uint16).numpy()
@@ -73,6 +137,22 @@ def cpu_baseline_step(cfg, weights, tokens):
     return dict(value=M / t_step, unit="tokens/s", cores=oracle.threads(), kind="oracle",
                 sample=f"{n_sample} of {nl} layers over all {M} rows ({t_layer:.2f} s each) + vocabulary projection and row phase "
                        f"of {n_rows} of {M} rows ({t_head:.2f} s), scaled linearly to a whole step ({t_step:.1f} s)")
+
+
+def cpu_baseline_selector(sample):
+    """The oracle's row phase on the sampled rows of the selector workload: its rate on the host cores,
+    and the check of the library's predictions and confidences for those rows."""
+    import numpy as np
+    import oracle
+    t0 = time.perf_counter()
+    o_pred, o_conf = oracle.row_phase(sample["logits_bits"], sample["mask_id"])
+    dt = time.perf_counter() - t0
+    same = bool(np.array_equal(o_pred, sample["pred"]))
+    rel = float((np.abs(sample["conf"].astype(np.float64) - o_conf) / o_conf).max())
+    assert same and rel <= 1e-3, f"selector rows differ from the oracle: predictions equal {same}, confidence error {rel}"
+    n = len(o_pred)
+    return dict(rows_per_s=n / dt, cores=oracle.threads(), kind="oracle", sample=f"{n} seeded rows of the workload ({dt:.3f} s)",
+                check=f"{n} sampled rows: predictions identical to the oracle's, confidences within {rel:.1e} (bar 1e-3)")
 
 
 def selector_extra(b, synth, torch):
@@ -118,8 +198,14 @@ def selector_extra(b, synth, torch):
     fast_ms = timed(fast, mask)
     fast_rows = int(mask[:, :L // 2].sum())
     all_ms = timed(sps, torch.ones_like(mask))
+    # a sample of the rated rows (their logits, and what the last timed call left for them) for the check
+    # against the oracle, which the CPU-baseline leg runs and times
+    idx = torch.nonzero(torch.ones_like(mask).view(-1)).view(-1)
+    idx = idx[torch.randperm(idx.numel(), generator=torch.Generator().manual_seed(7))[:256].to(idx.device)]
+    sample = dict(rows=idx.cpu().numpy(), logits_bits=logits.view(B * L, V)[idx].cpu().view(torch.uint16).numpy(),
+                  pred=pred.view(-1)[idx].cpu().numpy(), conf=conf.view(-1)[idx].cpu().numpy(), mask_id=cfg["mask_id"])
     del logits
-    return dict(workload="selector 16x2048x126464 bf16, 50% masked, slow stage k=1", ms=ms,
+    return dict(sample=sample, workload="selector 16x2048x126464 bf16, 50% masked, slow stage k=1", ms=ms,
                 masked_rows=n_masked, achieved_GBs=bytes_alg / ms / 1e6, frac_hbm=bytes_alg / ms / 1e6 / HBM_PEAK_GBS,
                 fast_stage_first_half={"ms": fast_ms, "masked_rows": fast_rows,
                                        "achieved_GBs": fast_rows * V * 2.0 / fast_ms / 1e6},
@@ -156,6 +242,8 @@ def main():
             dst = torch.empty_like(src)
             torch.mul(src, 1.0, out=dst)
             torch.cuda.synchronize()
+        sample = sel.pop("sample")
+        sel["cpu_baseline"] = cpu_baseline_selector(sample)
         print(json.dumps({"metric": "selector rows/s (fused softmax max/argmax + SlowFast commit)",
                           "value": sel["masked_rows"] / (sel["ms"] * 1e-3), "unit": "masked rows/s", "n_gpus": 1,
                           "dtype": "bf16 logits, fp32 arithmetic", "data": "synthetic",
@@ -163,7 +251,7 @@ def main():
                           "roofline": {"kernel": "row_phase_kernel", "bound": "hbm", "achieved": sel["achieved_GBs"],
                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sel["frac_hbm"], "traffic": None},
                           "ms": sel["ms"], "fast_stage_first_half": sel["fast_stage_first_half"],
-                          "all_rows_masked": sel["all_rows_masked"]}))
+                          "all_rows_masked": sel["all_rows_masked"], "cpu_baseline": sel["cpu_baseline"]}))
         return
     cfg = synth.CONFIGS[args.workload]
     mc = synth.model_config(cfg)
@@ -182,14 +270,20 @@ def main():
         model.step(tokens, mask, prev, sps, out)
     torch.cuda.synchronize()
     model.profile_begin(args.steps * mc["n_layers"])
+    # the library works on the stream that is current here, so these events bracket its steps
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    evs[0].record()
+    for i in range(args.steps):
         model.step(tokens, mask, prev, sps, out)
+        evs[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     k_ms, k_launches = model.profile_end()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    per_step = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps))
+    ms_median = per_step[len(per_step) // 2]
     assert int(mask.sum()) == B * G - B * (args.steps + args.warmup), "every step must commit one token per sequence"
 
     flops = step_flops(mc, B, L, vocab_rows=B * G)          # slow-stage window = the whole generated region
@@ -211,14 +305,23 @@ def main():
                                f"{mc['head_dim']} ffn={mc['d_ffn']} V={mc['vocab']}, batch {B}, {P} prompt + {G} "
                                f"masked (L={L}), seeded N(0,0.02) bf16 weights, slow stage k_slow=1",
                    "global_batch": B, "seq_len": L},
+        "ms_per_step_median_hip_events": ms_median,
         "step_tflops": flops / 1e12,
         "step_mfma_frac": flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "roofline": {"kernel": ("gemm_il_kernel<256,192,2x2 waves,BK 32,5 stages,SwiGLU>" if B * L == 512 else
-                                "gemm_il_kernel<tile picked by the planner for this M,SwiGLU>")
-                               + " (gate/up projection, one launch per layer)",
+        "roofline": {"kernel": gemm_kernel_name(b, 1, B * L, 2 * mc["d_ffn"], mc["d_model"], "SwiGLU")
+                               + " (gate/up projection, one launch per layer; the plan the library reports for this shape)",
                      "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+                     "traffic_source": None if traffic is None else
+                     "profiles/step_llada8b_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this "
+                     "command, scaled by a 1 GiB copy); not measured in this run",
                      "avg_launch_ms": k_avg_ms, "launches": k_launches, "flops_per_launch": k_flops},
+        "gemm_plans": {name: b.gemm_plan(epi, m, n, k) for name, epi, m, n, k in [
+            ("qkv_rope", 4 if mc["head_dim"] == 128 else 3, B * L, 3 * mc["d_model"], mc["d_model"]),
+            ("o_proj", 2, B * L, mc["d_model"], mc["d_model"]),
+            ("gate_up_swiglu", 1, B * L, 2 * mc["d_ffn"], mc["d_model"]),
+            ("down", 2, B * L, mc["d_model"], mc["d_ffn"]),
+            ("vocab_rowstats", 5, B * G, mc["vocab"], mc["d_model"])]},
     }
 
     if args.pmc_copy:
@@ -339,9 +442,14 @@ def main():
                       "response_cache_interval = 5"}
         result["cpu_baseline"] = cpu_baseline_step(mc, weights, tokens0)
         model.close()
-        del model, weights
+        del model
+        torch.cuda.empty_cache()
+        if args.workload == "llada8b":
+            result["long_batch"] = long_batch_extra(b, synth, torch, weights, mc)
+        del weights
         torch.cuda.empty_cache()
         result["selector"] = selector_extra(b, synth, torch)
+        result["selector"]["cpu_baseline"] = cpu_baseline_selector(result["selector"].pop("sample"))
     print(json.dumps(result))
 
 
