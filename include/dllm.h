@@ -319,6 +319,17 @@ int dllm_op_rope(void *hip_stream, void *qkv, int32_t B, int32_t L, int32_t H, i
  * DLLM_EINVAL if the fused kernel does not cover the shape (dh not 64/128, (H*dh) % 64 != 0). */
 int dllm_op_linear_qkv_rope(void *hip_stream, const void *A, const void *W, void *qkv, float *table,
                             int32_t B, int32_t L, int32_t H, int32_t dh, float theta);
+/* dllm_op_linear_qkv_rope for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same product, same
+ * kernels and bit-identical output, but the rotary table lives in a 4 MiB array built into the library
+ * (one copy per GPU, resident until the process ends) instead of caller-provided scratch; the call
+ * allocates nothing on the device.  Limit: L * dh / 2 <= 524288 table entries, i.e. L <= 8192 at
+ * head_dim 128 and L <= 16384 at head_dim 64 (DLLM_EINVAL beyond, nothing enqueued).  Every call on a GPU
+ * rewrites that GPU's one table: calls that may overlap on the same GPU (different streams or threads,
+ * unless every one of them uses the same L, dh and theta) race and must be serialised by the caller.
+ * Other arguments and errors as dllm_op_linear_qkv_rope. */
+int dllm_op_linear_qkv_rope_static(void *hip_stream, const void *A, const void *W, void *qkv, int32_t B, int32_t L,
+                                   int32_t H, int32_t dh, float theta);
 /* Non-causal attention: qkv bf16 [B*L][3*H*dh] -> out bf16 [B*L][H*dh]. */
 int dllm_op_attention(void *hip_stream, const void *qkv, void *out, int32_t B, int32_t L, int32_t H, int32_t dh);
 

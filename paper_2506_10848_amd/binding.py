@@ -64,7 +64,7 @@ class StepStat(C.Structure):
 
 EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_step_cached", "dllm_decode", "dllm_decode_low_confidence", "dllm_set_fused_selector", "dllm_sync_status", "dllm_debug_reload_env", "dllm_debug_gemm_plan", "dllm_debug_logits",
            "dllm_debug_rows", "dllm_profile_begin", "dllm_profile_end", "dllm_forward", "dllm_select", "dllm_op_linear", "dllm_op_linear_swiglu",
-           "dllm_op_add_rmsnorm", "dllm_op_rope", "dllm_op_linear_qkv_rope", "dllm_op_attention"]
+           "dllm_op_add_rmsnorm", "dllm_op_rope", "dllm_op_linear_qkv_rope", "dllm_op_linear_qkv_rope_static", "dllm_op_attention"]
 
 _lib = None
 
@@ -333,6 +333,14 @@ def op_linear_qkv_rope(A, W, B: int, L: int, H: int, dh: int, theta: float):
     table = torch.empty((L, dh // 2, 2), dtype=torch.float32, device=A.device)
     _check(lib().dllm_op_linear_qkv_rope(_stream(), _ptr(A), _ptr(W), _ptr(qkv), _ptr(table), B, L, H, dh,
                                          C.c_float(theta)))
+    return qkv
+
+
+def op_linear_qkv_rope_static(A, W, qkv, B: int, L: int, H: int, dh: int, theta: float):
+    """dllm_op_linear_qkv_rope_static: writes into the caller's qkv [B*L, 3*H*dh]; nothing is allocated."""
+    _dev(A, torch.bfloat16, "A"); _dev(W, torch.bfloat16, "W"); _dev(qkv, torch.bfloat16, "qkv")
+    assert qkv.shape == (B * L, 3 * H * dh)
+    _check(lib().dllm_op_linear_qkv_rope_static(_stream(), _ptr(A), _ptr(W), _ptr(qkv), B, L, H, dh, C.c_float(theta)))
     return qkv
 
 

@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -446,6 +447,34 @@ struct Controller {
     }
 };
 
+}  // namespace
+
+// ---- built-in scratch of the entry point that allocates nothing --------------------------------
+// One rotary table, (cos, sin) for up to 8192 positions x 64 pairs (head_dim 128) = 4 MiB, resident
+// on every GPU the library runs on until the process ends.  `scratch` names the symbol, not a device
+// address: host code uses only the address that hipGetSymbolAddress returns for the current device.
+constexpr size_t kStaticRopeEntries = (size_t)8192 * 64;
+static __device__ __align__(256) float2 scratch[kStaticRopeEntries];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static float2 *g_scratch_ptr[kMaxDevices] = {};  // per device, set on the first call with that device current
+
+namespace {
+int static_scratch(float2 **out)
+{
+    int dev = -1;
+    HIP_TRY(nullptr, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, DLLM_EINVAL, "device index %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(nullptr, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(nullptr, DLLM_EHIP, "hipGetSymbolAddress returned a null address for the built-in scratch");
+        g_scratch_ptr[dev] = static_cast<float2 *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return DLLM_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -987,6 +1016,29 @@ int dllm_op_linear_qkv_rope(void *hip_stream, const void *A, const void *W, void
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     HIP_TRY(nullptr, launch_rope_table(st, reinterpret_cast<float2 *>(table), L, dh, theta));
     HIP_TRY(nullptr, launch_gemm_qkv_rope(st, A, W, qkv, M, d, dh, reinterpret_cast<const float2 *>(table), L));
+    return DLLM_OK;
+}
+
+int dllm_op_linear_qkv_rope_static(void *hip_stream, const void *A, const void *W, void *qkv, int32_t B, int32_t L,
+                                   int32_t H, int32_t dh, float theta)
+{
+    if (!A || !W || !qkv) return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_qkv_rope_static: null argument");
+    if (!aligned16(A) || !aligned16(W) || !aligned16(qkv))
+        return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_qkv_rope_static: pointers must be 16-byte aligned");
+    if (B < 1 || L < 1 || H < 1 || !(theta > 0.0f) || (long)B * L > (1L << 24) || (long)H * dh > (1L << 20))
+        return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_qkv_rope_static: bad shape");
+    const int M = B * L, d = H * dh;
+    if (!gemm_qkv_rope_supported(M, d, dh))
+        return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_qkv_rope_static: shape not covered by the fused kernel");
+    if ((size_t)L * (size_t)(dh / 2) > kStaticRopeEntries)
+        return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_qkv_rope_static: the rotary table of L = %d positions x %d pairs "
+                                          "exceeds the built-in scratch of %zu entries (L <= %zu at this head_dim)",
+                    L, dh / 2, kStaticRopeEntries, kStaticRopeEntries / (size_t)(dh / 2));
+    float2 *table = nullptr;
+    if (int rc = static_scratch(&table)) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    HIP_TRY(nullptr, launch_rope_table(st, table, L, dh, theta));
+    HIP_TRY(nullptr, launch_gemm_qkv_rope(st, A, W, qkv, M, d, dh, table, L));
     return DLLM_OK;
 }
 
