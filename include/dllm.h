@@ -66,6 +66,8 @@ typedef struct {
 /* Device pointers to bf16 weights; the library reads them in place and never
  * copies or frees them.  Per-layer members are host arrays of n_layers device
  * pointers (the arrays themselves are copied at create).
+ * (dllm_create also makes panel-major copies of the projection matrices for its own use, see "Panel-major
+ * layout" below; the caller's arrays stay in use for shapes those copies do not serve and must stay alive.)
  *   embed      [vocab][d_model]     token embedding ([MASK] has its own row)
  *   lm_head    [vocab][d_model]
  *   final_norm [d_model]
@@ -306,6 +308,24 @@ int dllm_op_linear(void *hip_stream, const void *A, const void *W, void *C, int3
 /* out[M][f] = silu(A Wg^T) * (A Wu^T) with W = [gate | up] rows, [2f][K]. */
 int dllm_op_linear_swiglu(void *hip_stream, const void *A, const void *W, void *out, int32_t M, int32_t f,
                           int32_t K);
+/* Panel-major layout.  Inside a step the library keeps the operands of its projections "panel-major": a
+ * matrix X[rows][K] (K % 32 == 0) stored as [K / 32][panel_rows][32], i.e. panel p holds elements
+ * [32 p, 32 p + 32) of every row and the 64-byte pieces of consecutive rows follow each other.  A tile's
+ * K-stage is then one contiguous block and every request to the L2 a whole 128-byte line (measured: tile
+ * copies at 115 instead of 65 GB/s per CU from the L2, 6.3 instead of 4.4 TB/s from HBM).  dllm_create
+ * makes panel-major copies of the projection weights whose reduction length is a multiple of 64 (so a
+ * handle holds those weights twice: 15 GB more at the LLaDA-8B shape) unless the environment variable
+ * DLLM_NO_PACK is set; the two calls below expose the layout for tests and timing.
+ *
+ * dst (bf16 [K / 32][rows][32]) = src (bf16 [rows][K]). */
+int dllm_op_pack_panels(void *hip_stream, const void *src, void *dst, int64_t rows, int32_t K);
+/* dllm_op_linear (swiglu == 0) or dllm_op_linear_swiglu (swiglu != 0, N counts gate + up rows) with operands in
+ * either layout: a_panel_rows 0 = A row-major [M][K], else A panel-major with that many rows per panel (>= M,
+ * A points at the first used row inside panel 0); w_panels != 0 = W panel-major [K / 32][N][32]; c_panel_rows
+ * (SwiGLU only, (N / 2) % 32 == 0) likewise for the output.  DLLM_EINVAL if a panel-major operand is given for
+ * a shape the asynchronous-copy kernel does not take (K % 64 != 0). */
+int dllm_op_linear_panels(void *hip_stream, const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K,
+                          int32_t swiglu, int32_t a_panel_rows, int32_t w_panels, int32_t c_panel_rows);
 /* x (fp32 [M][d], in/out) += sum of n_partials fp32 [M][d] slabs (0 to 8);
  * h (bf16 [M][d]) = RMSNorm(x) * gain. */
 int dllm_op_add_rmsnorm(void *hip_stream, float *x, const float *partials, int32_t n_partials,

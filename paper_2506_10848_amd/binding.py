@@ -63,7 +63,7 @@ class StepStat(C.Structure):
 
 
 EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_step_cached", "dllm_decode", "dllm_decode_low_confidence", "dllm_set_fused_selector", "dllm_sync_status", "dllm_debug_reload_env", "dllm_debug_gemm_plan", "dllm_debug_logits",
-           "dllm_debug_rows", "dllm_profile_begin", "dllm_profile_end", "dllm_forward", "dllm_select", "dllm_op_linear", "dllm_op_linear_swiglu",
+           "dllm_debug_rows", "dllm_profile_begin", "dllm_profile_end", "dllm_forward", "dllm_select", "dllm_op_linear", "dllm_op_linear_swiglu", "dllm_op_pack_panels", "dllm_op_linear_panels",
            "dllm_op_add_rmsnorm", "dllm_op_rope", "dllm_op_linear_qkv_rope", "dllm_op_linear_qkv_rope_static", "dllm_op_attention"]
 
 _lib = None
@@ -334,6 +334,26 @@ def op_linear_qkv_rope(A, W, B: int, L: int, H: int, dh: int, theta: float):
     _check(lib().dllm_op_linear_qkv_rope(_stream(), _ptr(A), _ptr(W), _ptr(qkv), _ptr(table), B, L, H, dh,
                                          C.c_float(theta)))
     return qkv
+
+
+def op_pack_panels(src):
+    """dllm_op_pack_panels: bf16 [rows, K] -> panel-major bf16 [K // 32, rows, 32]."""
+    _dev(src, torch.bfloat16, "src")
+    rows, K = src.shape
+    dst = torch.empty((K // 32, rows, 32), dtype=torch.bfloat16, device=src.device)
+    _check(lib().dllm_op_pack_panels(_stream(), _ptr(src), _ptr(dst), C.c_int64(rows), K))
+    return dst
+
+
+def op_linear_panels(A, W, M: int, N: int, K: int, swiglu: bool, a_panel_rows: int, w_panels: bool, c_panel_rows: int):
+    """dllm_op_linear_panels; A / W are device tensors in whichever layout the flags say.  Returns C as
+    [M, N] (or [M, N/2]; panel-major output: [N/2 // 32, c_panel_rows, 32])."""
+    n_out = N // 2 if swiglu else N
+    shape = (n_out // 32, c_panel_rows, 32) if c_panel_rows else (M, n_out)
+    out = torch.zeros(shape, dtype=torch.bfloat16, device=A.device)
+    _check(lib().dllm_op_linear_panels(_stream(), _ptr(A), _ptr(W), _ptr(out), M, N, K, int(swiglu), a_panel_rows,
+                                       int(w_panels), c_panel_rows))
+    return out
 
 
 def op_linear_qkv_rope_static(A, W, qkv, B: int, L: int, H: int, dh: int, theta: float):

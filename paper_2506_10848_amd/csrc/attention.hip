@@ -56,7 +56,7 @@ template <int DH, int KVSPLIT>
 __global__ __launch_bounds__(kThreads, 2) void attention_kernel(const uint16_t *__restrict__ qsrc,
                                                              const uint16_t *__restrict__ kvsrc,
                                                              uint16_t *__restrict__ out, int L, int H, int nq,
-                                                             SeqRows rows)
+                                                             SeqRows rows, int out_panel_rows)
 {
     constexpr int KSTEPS = DH / 16;  // MFMA K steps over the head dimension
     constexpr int DSUB = DH / 32;    // 32-row sub-tiles of O^T
@@ -289,7 +289,11 @@ __global__ __launch_bounds__(kThreads, 2) void attention_kernel(const uint16_t *
     const float inv = 1.0f / (l_tot * a0 + l1 * a1);
     const int q = q0 + l32;
     if (q < Lq) {
-        uint16_t *op = out + ((size_t)qfirst + q) * d + (size_t)h * DH;
+        // row-major: out[row][h * DH + dim]; panel-major: panel (h * DH + dim) / 32, 32 elements per row
+        const size_t orow = (size_t)qfirst + q;
+        uint16_t *op = out_panel_rows ? out + (((size_t)h * (DH / 32)) * out_panel_rows + orow) * 32
+                                      : out + orow * d + (size_t)h * DH;
+        const size_t sub_pitch = out_panel_rows ? (size_t)out_panel_rows * 32 - 32 : 0;  // added per 32-dim sub-tile
 #pragma unroll
         for (int i = 0; i < DSUB; ++i)
 #pragma unroll
@@ -305,14 +309,14 @@ __global__ __launch_bounds__(kThreads, 2) void attention_kernel(const uint16_t *
                 uint2 w;
                 w.x = pack_bf16x2(y[0], y[1]);
                 w.y = pack_bf16x2(y[2], y[3]);
-                *reinterpret_cast<uint2 *>(op + dim) = w;
+                *reinterpret_cast<uint2 *>(op + dim + i * sub_pitch) = w;
             }
     }
 }
 
 template <int DH, int KVSPLIT>
 hipError_t launch_split(hipStream_t stream, const void *q, const void *kv, void *out, int B, int Lk, int H,
-                        const SeqRows &rows, int max_count)
+                        const SeqRows &rows, int max_count, int out_panel_rows)
 {
     constexpr int QT = 128 / KVSPLIT;
     const size_t lds = sizeof(Smem<DH, KVSPLIT>);
@@ -325,41 +329,43 @@ hipError_t launch_split(hipStream_t stream, const void *q, const void *kv, void 
     if (attr != hipSuccess) return attr;
     const int nq = (max_count + QT - 1) / QT;
     hipLaunchKernelGGL(kern, dim3(nq * H * B), dim3(kThreads), lds, stream, (const uint16_t *)q, (const uint16_t *)kv,
-                       (uint16_t *)out, Lk, H, nq, rows);
+                       (uint16_t *)out, Lk, H, nq, rows, out_panel_rows);
     return hipGetLastError();
 }
 
 template <int DH>
 hipError_t launch_dh(hipStream_t stream, const void *q, const void *kv, void *out, int B, int Lk, int H,
-                     const SeqRows &rows)
+                     const SeqRows &rows, int out_panel_rows)
 {
     int max_count = 0;
     for (int b = 0; b < B; ++b) max_count = rows.count[b] > max_count ? rows.count[b] : max_count;
     if (max_count == 0) return hipSuccess;
     // few workgroups: split the keys inside a workgroup to shorten the chain
     const long wgs128 = (long)((max_count + 127) / 128) * H * B;
-    if (wgs128 < 1024) return launch_split<DH, 2>(stream, q, kv, out, B, Lk, H, rows, max_count);
-    return launch_split<DH, 1>(stream, q, kv, out, B, Lk, H, rows, max_count);
+    if (wgs128 < 1024) return launch_split<DH, 2>(stream, q, kv, out, B, Lk, H, rows, max_count, out_panel_rows);
+    return launch_split<DH, 1>(stream, q, kv, out, B, Lk, H, rows, max_count, out_panel_rows);
 }
 
 }  // namespace
 
 hipError_t launch_attention_rows(hipStream_t stream, const void *q, const void *kv, void *out, int B, int Lk, int H,
-                                 int dh, const SeqRows &rows)
+                                 int dh, const SeqRows &rows, int out_panel_rows)
 {
     if (B < 1 || B > DLLM_MAX_BATCH) return hipErrorInvalidValue;
-    if (dh == 128) return launch_dh<128>(stream, q, kv, out, B, Lk, H, rows);
-    if (dh == 64) return launch_dh<64>(stream, q, kv, out, B, Lk, H, rows);
+    if (dh == 128) return launch_dh<128>(stream, q, kv, out, B, Lk, H, rows, out_panel_rows);
+    if (dh == 64) return launch_dh<64>(stream, q, kv, out, B, Lk, H, rows, out_panel_rows);
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_attention(hipStream_t stream, const void *qkv, void *out, int B, int L, int H, int dh)
+hipError_t launch_attention(hipStream_t stream, const void *qkv, void *out, int B, int L, int H, int dh,
+                            int out_panel_rows)
 {
     if (B <= DLLM_MAX_BATCH) {
         SeqRows rows;
         for (int b = 0; b < B; ++b) { rows.first[b] = b * L; rows.count[b] = L; }
-        return launch_attention_rows(stream, qkv, qkv, out, B, L, H, dh, rows);
+        return launch_attention_rows(stream, qkv, qkv, out, B, L, H, dh, rows, out_panel_rows);
     }
+    if (out_panel_rows) return hipErrorInvalidValue;
     // more sequences than the row table holds (test hook only): one launch per group
     for (int b0 = 0; b0 < B; b0 += DLLM_MAX_BATCH) {
         const int nb = B - b0 < DLLM_MAX_BATCH ? B - b0 : DLLM_MAX_BATCH;

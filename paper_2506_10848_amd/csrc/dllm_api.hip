@@ -3,6 +3,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <mutex>
@@ -57,6 +58,11 @@ struct dllm_handle {
     hipStream_t stream;
     const void *embed, *lm_head, *final_norm;
     std::vector<const void *> attn_norm, wqkv, wo, ffn_norm, w_gate_up, w_down;
+    // panel-major copies of the projection weights (see GemmLayout), made at create; null where the reduction
+    // length is not a multiple of 64 (those products run on the register-staged kernel from the caller's rows)
+    const void *lm_head_p = nullptr;
+    std::vector<const void *> wqkv_p, wo_p, w_gate_up_p, w_down_p;
+    bool packed_d = false, packed_f = false;  // weights with K = d_model / K = d_ffn have panel-major copies
     Workspace ws;
     std::vector<void *> allocs;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
@@ -177,21 +183,44 @@ int check_commit_list(dllm_handle *h, const dllm_commit_list *o, CommitOut *c)
 // h_row of ws.h; abs_row is the batch row (b * L + i) of the first of them.  With the fused selector
 // and a mask, the projection leaves per-slice row statistics instead of logits and the merge
 // kernel turns them into ws.pred / ws.conf at the masked rows of the windows.
-int vocab_rows(dllm_handle *h, long h_row, long abs_row, int n, int L, const uint8_t *mask, const SelectArgs *win)
+// h_panel_rows: 0, or the rows per panel of a panel-major ws.h.
+int vocab_rows(dllm_handle *h, long h_row, long abs_row, int n, int L, const uint8_t *mask, const SelectArgs *win,
+               int h_panel_rows)
 {
     const dllm_config &c = h->cfg;
     Workspace &w = h->ws;
+    // the first of the n rows: 64 bytes per row inside panel 0, or d_model elements per row
+    const uint16_t *A = h_panel_rows ? w.h + h_row * 32 : w.h + h_row * c.d_model;
+    const void *W = h_panel_rows ? h->lm_head_p : h->lm_head;
+    const GemmLayout lay{h_panel_rows, h_panel_rows ? c.vocab : 0, 0};
     if (h->fused_selector && mask && win) {
         int parts = 0;
-        HIP_TRY(h, launch_gemm_rowstats(h->stream, w.h + h_row * c.d_model, h->lm_head, w.rowstats, n, c.vocab, c.d_model,
-                                        c.mask_id, &parts));
+        HIP_TRY(h, launch_gemm_rowstats(h->stream, A, W, w.rowstats, n, c.vocab, c.d_model, c.mask_id, &parts, lay));
         HIP_TRY(h, launch_rowstats_merge(h->stream, w.rowstats, parts, n, (int)abs_row, L, mask, *win, w.pred, w.conf));
     } else {
         if (int rc = ensure_logits(h)) return rc;
-        HIP_TRY(h, launch_gemm(h->stream, kEpiBf16, w.h + h_row * c.d_model, h->lm_head, w.logits + abs_row * (long)c.vocab,
-                               n, c.vocab, c.d_model));
+        HIP_TRY(h, launch_gemm(h->stream, kEpiBf16, A, W, w.logits + abs_row * (long)c.vocab, n, c.vocab, c.d_model,
+                               kGemmMaxSplits, lay));
     }
     return DLLM_OK;
+}
+
+// Which activations of a forward over `rows` rows are kept panel-major: those that feed products with
+// reduction length d_model (normalised hidden states, attention output) and d_ffn (SwiGLU output), each only
+// if the handle has panel-major weights for them and every such product runs on the asynchronous-copy kernel.
+struct PanelChoice {
+    int d_rows, f_rows;  // rows per panel, 0 = row-major
+};
+PanelChoice pick_panels(const dllm_handle *h, int rows)
+{
+    const dllm_config &c = h->cfg;
+    const int d = c.d_model, f = c.d_ffn;
+    const int qkv_epi = gemm_qkv_rope_supported(rows, d, c.head_dim) ? (c.head_dim == 128 ? 4 : 3) : (int)kEpiBf16;
+    const bool pd = h->packed_d && gemm_async_copy_path(qkv_epi, rows, 3 * d, d) &&
+                    gemm_async_copy_path(kEpiPartial, rows, d, d) && gemm_async_copy_path(kEpiSwiglu, rows, 2 * f, d) &&
+                    gemm_async_copy_path(kEpiBf16, rows, c.vocab, d) && gemm_async_copy_path(5, rows, c.vocab, d);
+    const bool pf = h->packed_f && gemm_async_copy_path(kEpiPartial, rows, d, f);
+    return PanelChoice{pd ? rows : 0, pf ? rows : 0};
 }
 
 // `win` (nullable): per-sequence windows; the vocabulary projection then only
@@ -206,30 +235,36 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const Sele
     HIP_TRY(h, launch_embed(st, tokens, nullptr, h->embed, w.x, M, d, c.vocab, w.bad_token));
     const int slabs = slab_limit(h, M);
     if (slabs < 1) return fail(h, DLLM_ESTATE, "the split-K workspace does not hold one slab of %d rows", M);
+    const PanelChoice pc = pick_panels(h, M);
+    const int pd = pc.d_rows, pf = pc.f_rows;
     int pending = 0;  // fp32 slabs waiting to be added to the residual stream
     for (int l = 0; l < c.n_layers; ++l) {
-        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->attn_norm[l], w.h, M, d, c.rms_eps));
+        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->attn_norm[l], w.h, M, d, c.rms_eps, pd));
+        const void *wqkv = pd ? h->wqkv_p[l] : h->wqkv[l];
         if (gemm_qkv_rope_supported(M, d, c.head_dim)) {
-            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, h->wqkv[l], w.qkv, M, d, c.head_dim, w.rope, L));
+            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, wqkv, w.qkv, M, d, c.head_dim, w.rope, L, nullptr,
+                                            GemmLayout{pd, pd ? 3 * d : 0, 0}));
         } else {
-            HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, h->wqkv[l], w.qkv, M, 3 * d, d));
+            HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, wqkv, w.qkv, M, 3 * d, d, kGemmMaxSplits, GemmLayout{pd, pd ? 3 * d : 0, 0}));
             HIP_TRY(h, launch_rope(st, w.qkv, w.rope, B, L, c.n_heads, c.head_dim, c.rope_theta));
         }
-        HIP_TRY(h, launch_attention(st, w.qkv, w.att, B, L, c.n_heads, c.head_dim));
+        HIP_TRY(h, launch_attention(st, w.qkv, w.att, B, L, c.n_heads, c.head_dim, pd));
         pending = gemm_num_splits(M, d, d, slabs);
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, M, d, d, slabs));
-        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->ffn_norm[l], w.h, M, d, c.rms_eps));
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, pd ? h->wo_p[l] : h->wo[l], w.partials, M, d, d, slabs,
+                               GemmLayout{pd, pd ? d : 0, 0}));
+        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->ffn_norm[l], w.h, M, d, c.rms_eps, pd));
         const bool prof = h->prof_on && h->prof_used < h->prof_cap;
         if (prof) HIP_TRY(h, hipEventRecord(h->prof_ev[2 * h->prof_used], st));
-        HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, h->w_gate_up[l], w.act, M, 2 * f, d));
+        HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, pd ? h->w_gate_up_p[l] : h->w_gate_up[l], w.act, M, 2 * f, d,
+                               kGemmMaxSplits, GemmLayout{pd, pd ? 2 * f : 0, pf}));
         if (prof) HIP_TRY(h, hipEventRecord(h->prof_ev[2 * h->prof_used++ + 1], st));
         pending = gemm_num_splits(M, d, f, slabs);
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, h->w_down[l], w.partials, M, d, f, slabs));
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, pf ? h->w_down_p[l] : h->w_down[l], w.partials, M, d, f, slabs,
+                               GemmLayout{pf, pf ? d : 0, 0}));
     }
-    HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, M, d, c.rms_eps));
+    HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, M, d, c.rms_eps, pd));
     if (!win) {
-        if (int rc = ensure_logits(h)) return rc;
-        HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, h->lm_head, w.logits, M, c.vocab, d));
+        if (int rc = vocab_rows(h, 0, 0, M, L, nullptr, nullptr, pd)) return rc;
     } else {
         // merge sequences whose windows make one contiguous run of rows (always true for B = 1)
         int b = 0;
@@ -242,7 +277,7 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const Sele
                 last = (long)e * L + win->w[e].hi;
                 ++e;
             }
-            if (int rc = vocab_rows(h, first, first, (int)(last - first + 1), L, mask, win)) return rc;
+            if (int rc = vocab_rows(h, first, first, (int)(last - first + 1), L, mask, win, pd)) return rc;
             b = e;
         }
     }
@@ -303,26 +338,33 @@ int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, con
     HIP_TRY(h, launch_embed(st, tokens, w.rows_d, h->embed, w.x, Ma, d, c.vocab, w.bad_token));
     const int slabs = slab_limit(h, Ma);
     if (slabs < 1) return fail(h, DLLM_ESTATE, "the split-K workspace does not hold one slab of %d rows", Ma);
+    const PanelChoice pc = pick_panels(h, Ma);
+    const int pd = pc.d_rows, pf = pc.f_rows;
     int pending = 0;
     for (int l = 0; l < c.n_layers; ++l) {
-        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->attn_norm[l], w.h, Ma, d, c.rms_eps));
+        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->attn_norm[l], w.h, Ma, d, c.rms_eps, pd));
+        const void *wqkv = pd ? h->wqkv_p[l] : h->wqkv[l];
+        const GemmLayout lq{pd, pd ? 3 * d : 0, 0};
         if (!any_skip) {
             // everything is recomputed: the projection writes straight into the layer's cache
-            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, h->wqkv[l], w.kv_cache[l], Ma, d, c.head_dim, w.rope, L, w.pos_d));
-            HIP_TRY(h, launch_attention_rows(st, w.kv_cache[l], w.kv_cache[l], w.att, B, L, c.n_heads, c.head_dim, sr));
+            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, wqkv, w.kv_cache[l], Ma, d, c.head_dim, w.rope, L, w.pos_d, lq));
+            HIP_TRY(h, launch_attention_rows(st, w.kv_cache[l], w.kv_cache[l], w.att, B, L, c.n_heads, c.head_dim, sr, pd));
         } else {
-            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, h->wqkv[l], w.qkv, Ma, d, c.head_dim, w.rope, L, w.pos_d));
+            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, wqkv, w.qkv, Ma, d, c.head_dim, w.rope, L, w.pos_d, lq));
             HIP_TRY(h, launch_scatter_kv(st, w.qkv, w.kv_cache[l], w.rows_d, Ma, d));
-            HIP_TRY(h, launch_attention_rows(st, w.qkv, w.kv_cache[l], w.att, B, L, c.n_heads, c.head_dim, sr));
+            HIP_TRY(h, launch_attention_rows(st, w.qkv, w.kv_cache[l], w.att, B, L, c.n_heads, c.head_dim, sr, pd));
         }
         pending = gemm_num_splits(Ma, d, d, slabs);
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, h->wo[l], w.partials, Ma, d, d, slabs));
-        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->ffn_norm[l], w.h, Ma, d, c.rms_eps));
-        HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, h->w_gate_up[l], w.act, Ma, 2 * f, d));
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, pd ? h->wo_p[l] : h->wo[l], w.partials, Ma, d, d, slabs,
+                               GemmLayout{pd, pd ? d : 0, 0}));
+        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->ffn_norm[l], w.h, Ma, d, c.rms_eps, pd));
+        HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, pd ? h->w_gate_up_p[l] : h->w_gate_up[l], w.act, Ma, 2 * f, d,
+                               kGemmMaxSplits, GemmLayout{pd, pd ? 2 * f : 0, pf}));
         pending = gemm_num_splits(Ma, d, f, slabs);
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, h->w_down[l], w.partials, Ma, d, f, slabs));
+        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, pf ? h->w_down_p[l] : h->w_down[l], w.partials, Ma, d, f, slabs,
+                               GemmLayout{pf, pf ? d : 0, 0}));
     }
-    HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, Ma, d, c.rms_eps));
+    HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, Ma, d, c.rms_eps, pd));
     // logits stay indexed by absolute row; the rows of a window are consecutive among the recomputed ones
     for (int b = 0; b < B; ++b) {
         const SeqWindow &sw = win.w[b];
@@ -332,7 +374,7 @@ int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, con
         for (int i = 0; i < sw.lo; ++i) first_cmp += !(skip && skip[(size_t)b * L + i]);
         for (int i = sw.lo; i <= sw.eval_hi; ++i)
             if (skip && skip[(size_t)b * L + i]) return fail(h, DLLM_EINVAL, "sequence %d: position %d is skipped but inside the window", b, i);
-        if (int rc = vocab_rows(h, first_cmp, first_abs, (int)n, L, mask, &win)) return rc;
+        if (int rc = vocab_rows(h, first_cmp, first_abs, (int)n, L, mask, &win, pd)) return rc;
     }
     if (!any_skip) { w.cache_valid = true; w.cache_B = B; w.cache_L = L; }
     h->last_B = B;
@@ -573,6 +615,31 @@ int dllm_create(const dllm_config *cfg, const dllm_weights *w, void *hip_stream,
         rc = fail(h, DLLM_EHIP, "dllm_create: hipEventCreate failed");
     if (rc == DLLM_OK && launch_rope_table(h->stream, s.rope, c.max_seq, c.head_dim, c.rope_theta) != hipSuccess)
         rc = fail(h, DLLM_EHIP, "dllm_create: rope table launch failed");
+    // panel-major copies of the weights (the caller's stay in use for shapes the asynchronous-copy kernel does not take)
+    if (rc == DLLM_OK && getenv("DLLM_NO_PACK") == nullptr) {
+        auto pack = [&](const void *src, size_t rows, size_t K, const void **dst) {
+            uint16_t *p = nullptr;
+            if (rc == DLLM_OK) rc = dev_alloc(h, &p, rows * K);
+            if (rc == DLLM_OK && launch_pack_panels(h->stream, src, p, rows, (int)K) != hipSuccess)
+                rc = fail(h, DLLM_EHIP, "dllm_create: weight packing launch failed");
+            *dst = p;
+        };
+        h->packed_d = d % 64 == 0;
+        h->packed_f = f % 64 == 0;
+        if (h->packed_d) {
+            pack(h->lm_head, c.vocab, d, &h->lm_head_p);
+            h->wqkv_p.assign(c.n_layers, nullptr); h->wo_p.assign(c.n_layers, nullptr); h->w_gate_up_p.assign(c.n_layers, nullptr);
+            for (int l = 0; l < c.n_layers; ++l) {
+                pack(h->wqkv[l], 3 * d, d, &h->wqkv_p[l]);
+                pack(h->wo[l], d, d, &h->wo_p[l]);
+                pack(h->w_gate_up[l], 2 * f, d, &h->w_gate_up_p[l]);
+            }
+        }
+        if (h->packed_f) {
+            h->w_down_p.assign(c.n_layers, nullptr);
+            for (int l = 0; l < c.n_layers; ++l) pack(h->w_down[l], d, f, &h->w_down_p[l]);
+        }
+    }
     if (rc == DLLM_OK && hipStreamSynchronize(h->stream) != hipSuccess)
         rc = fail(h, DLLM_EHIP, "dllm_create: stream synchronize failed");
     if (rc != DLLM_OK) {
@@ -980,6 +1047,33 @@ int dllm_op_linear_swiglu(void *hip_stream, const void *A, const void *W, void *
     int rc = check_linear(A, W, out, M, f, K, "dllm_op_linear_swiglu");
     if (rc) return rc;
     HIP_TRY(nullptr, launch_gemm(static_cast<hipStream_t>(hip_stream), kEpiSwiglu, A, W, out, M, 2 * f, K));
+    return DLLM_OK;
+}
+
+int dllm_op_pack_panels(void *hip_stream, const void *src, void *dst, int64_t rows, int32_t K)
+{
+    if (!src || !dst || !aligned16(src) || !aligned16(dst)) return fail(nullptr, DLLM_EINVAL, "dllm_op_pack_panels: null or misaligned pointer");
+    if (rows < 1 || K < 32 || K % 32) return fail(nullptr, DLLM_EINVAL, "dllm_op_pack_panels: need rows >= 1 and K a positive multiple of 32");
+    HIP_TRY(nullptr, launch_pack_panels(static_cast<hipStream_t>(hip_stream), src, dst, (size_t)rows, K));
+    return DLLM_OK;
+}
+
+int dllm_op_linear_panels(void *hip_stream, const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K,
+                          int32_t swiglu, int32_t a_panel_rows, int32_t w_panels, int32_t c_panel_rows)
+{
+    int rc = check_linear(A, W, C, M, N, K, "dllm_op_linear_panels");
+    if (rc) return rc;
+    if (a_panel_rows < 0 || c_panel_rows < 0 || (a_panel_rows && a_panel_rows < M) || (c_panel_rows && c_panel_rows < M))
+        return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_panels: panel rows must be 0 or >= M");
+    if (c_panel_rows && !swiglu) return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_panels: only the SwiGLU output can be panel-major");
+    if (swiglu && (N % 2)) return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_panels: SwiGLU needs an even number of W rows");
+    if (c_panel_rows && (N / 2) % 32) return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_panels: a panel-major output needs N / 2 %% 32 == 0");
+    const GemmEpilogue epi = swiglu ? kEpiSwiglu : kEpiBf16;
+    if ((a_panel_rows || w_panels || c_panel_rows) && !gemm_async_copy_path(epi, M, N, K))
+        return fail(nullptr, DLLM_EINVAL, "dllm_op_linear_panels: panel-major operands need the asynchronous-copy kernel "
+                                          "(K %% 64 == 0, operands below 4 GB, DLLM_GEMM_FALLBACK unset)");
+    HIP_TRY(nullptr, launch_gemm(static_cast<hipStream_t>(hip_stream), epi, A, W, C, M, N, K, kGemmMaxSplits,
+                                 GemmLayout{a_panel_rows, w_panels ? N : 0, c_panel_rows}));
     return DLLM_OK;
 }
 

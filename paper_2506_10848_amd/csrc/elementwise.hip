@@ -44,10 +44,12 @@ __global__ __launch_bounds__(kThreads) void scatter_kv_kernel(const uint16_t *__
 }
 
 // x += sum_s partials[s];  h = bf16( x * rsqrt(mean(x^2) + eps) * gain ).  d % 4 == 0.
+// h_panel_rows != 0: h is written panel-major, [d / 32][h_panel_rows][32] (the layout the GEMMs copy fastest).
 __global__ __launch_bounds__(kThreads) void add_rmsnorm_kernel(float *__restrict__ x,
                                                                const float *__restrict__ partials, int n_partials,
                                                                size_t slab, const uint16_t *__restrict__ gain,
-                                                               uint16_t *__restrict__ h, int d, float eps)
+                                                               uint16_t *__restrict__ h, int d, float eps,
+                                                               int h_panel_rows)
 {
     __shared__ float wsum[kThreads / kWave];
     const int r = blockIdx.x;
@@ -83,7 +85,10 @@ __global__ __launch_bounds__(kThreads) void add_rmsnorm_kernel(float *__restrict
         uint2 o;
         o.x = pack_bf16x2(v.x * inv * bf16_lo(g.x), v.y * inv * bf16_hi(g.x));
         o.y = pack_bf16x2(v.z * inv * bf16_lo(g.y), v.w * inv * bf16_hi(g.y));
-        hr[c] = o;
+        if (h_panel_rows)  // elements 4c .. 4c+3 of row r: panel c / 8, 8-byte slot c % 8 of the row's 64 bytes
+            reinterpret_cast<uint2 *>(h)[((size_t)(c >> 3) * h_panel_rows + r) * 8 + (c & 7)] = o;
+        else
+            hr[c] = o;
     }
 }
 
@@ -161,10 +166,11 @@ hipError_t launch_scatter_kv(hipStream_t stream, const void *src, void *dst, con
 }
 
 hipError_t launch_add_rmsnorm(hipStream_t stream, float *x, const float *partials, int n_partials, const void *gain,
-                              void *h, int M, int d, float eps)
+                              void *h, int M, int d, float eps, int h_panel_rows)
 {
+    if (h_panel_rows && (d % 32 || h_panel_rows < M)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(add_rmsnorm_kernel, dim3(M), dim3(kThreads), 0, stream, x, partials, n_partials,
-                       (size_t)M * d, (const uint16_t *)gain, (uint16_t *)h, d, eps);
+                       (size_t)M * d, (const uint16_t *)gain, (uint16_t *)h, d, eps, h_panel_rows);
     return hipGetLastError();
 }
 

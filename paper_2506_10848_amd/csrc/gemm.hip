@@ -56,6 +56,7 @@
 #include <map>
 #include <mutex>
 #include <tuple>
+#include <type_traits>
 
 #include "internal.h"
 
@@ -138,6 +139,10 @@ struct RopeArgs {
     const int32_t *pos;  // nullable: position of every row (rows of a gathered subset)
     union { int L; int parts; };
     union { int rope_cols; int mask_id; };
+    // Operand layouts (see GemmLayout): byte distance between consecutive rows and between consecutive
+    // 32-element K panels of A and of W, and the panel rows of a panel-major SwiGLU output (0: row-major).
+    uint32_t a_row_pitch, a_panel_pitch, w_row_pitch, w_panel_pitch;
+    int c_panel_rows;
 };
 constexpr int kEpiRope64 = 3, kEpiRope128 = 4;  // head_dim is a compile-time constant of the epilogue
 constexpr int kEpiRowStats = 5;
@@ -240,7 +245,10 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
                         y[e] = g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;  // 1 ulp reciprocal, far below the bf16 rounding
                     }
                     if (GUARD && (row >= M || col >= n_out)) continue;
-                    uint16_t *p = C + (size_t)row * n_out + col;
+                    // panel-major: element (row, col) sits at ((col / 32) * panel_rows + row) * 32 + col % 32
+                    uint16_t *p = rope.c_panel_rows
+                                      ? C + ((size_t)(col >> 5) * rope.c_panel_rows + row) * 32 + (col & 31)
+                                      : C + (size_t)row * n_out + col;
                     if (!GUARD || (col + 3 < n_out && (n_out & 3) == 0)) {
                         uint2 w;
                         w.x = pack_bf16x2(y[0], y[1]);
@@ -375,6 +383,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
 
     // copy instruction q = wave + NW * t moves LDS rows [q * RPI, (q + 1) * RPI); lane l lands on row
     // l / CPR, slot l % CPR of that group and therefore fetches the chunk that the swizzle puts there
+    // An operand is row-major (row pitch = K * 2 bytes, the 32-element K panels of a row follow each
+    // other: panel pitch 64) or panel-major (panel p holds elements [32 p, 32 p + 32) of every row: row pitch
+    // 64, panel pitch = rows * 64).  Chunk c of a stage's row (16 bytes each) is in panel c / 4, at c % 4.
     const int lrow = lane / CPR, lslot = lane % CPR;
     uint32_t goff[LOADS];  // byte offsets into A or W; rows past the edge are clamped
 #pragma unroll
@@ -382,14 +393,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
         const int q = wave + NW * t, r = q * RPI + lrow;
         const int swz = BK == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3);
         const int grow = q < A_NI ? min(m0 + r, M - 1) : w_global_row<EPI>(r - BM, n0, N);
-        goff[t] = (uint32_t)grow * (uint32_t)K * 2u + (lslot ^ swz) * 16;
+        const int chunk = lslot ^ swz;
+        const uint32_t row_pitch = q < A_NI ? rope.a_row_pitch : rope.w_row_pitch;
+        const uint32_t panel_pitch = q < A_NI ? rope.a_panel_pitch : rope.w_panel_pitch;
+        goff[t] = (uint32_t)grow * row_pitch + (uint32_t)(chunk >> 2) * panel_pitch + (chunk & 3) * 16;
     }
-    const char *Ab = reinterpret_cast<const char *>(A) + (size_t)kbeg * 2;
-    const char *Wb = reinterpret_cast<const char *>(W) + (size_t)kbeg * 2;
+    const size_t a_stage = (size_t)(BK / 32) * rope.a_panel_pitch, w_stage = (size_t)(BK / 32) * rope.w_panel_pitch;
+    const char *Ab = reinterpret_cast<const char *>(A) + (size_t)(kbeg / 32) * rope.a_panel_pitch;
+    const char *Wb = reinterpret_cast<const char *>(W) + (size_t)(kbeg / 32) * rope.w_panel_pitch;
     const uint32_t lds0 = lds_addr_of(smem) + wave * 1024;
 #define DLLM_COPY(t_, stage_, slot_)                                                             \
     do {                                                                                         \
-        const char *b_ = ((wave + NW * (t_)) < A_NI ? Ab : Wb) + (size_t)(stage_) * (BK * 2);    \
+        const bool a_ = (wave + NW * (t_)) < A_NI;                                               \
+        const char *b_ = (a_ ? Ab : Wb) + (size_t)(stage_) * (a_ ? a_stage : w_stage);           \
         async_load16(b_, goff[t_], lds0 + (slot_) * (STAGE * 16) + (t_) * (NW * 1024));          \
     } while (0)
 
@@ -408,6 +424,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
     // power limited, so the cycles and the energy go to the tiles that have rows)
     // (not in the 256x256 tile, whose 256 accumulator registers leave no room for one more value)
     constexpr bool kSkipEmpty = BM * BN < 256 * 256;
+    constexpr bool kEarlyReads = true;
     const int tm_valid = kSkipEmpty ? __builtin_amdgcn_readfirstlane(min(TM, max(0, (M - m0 - wm * WTM + 31) / 32))) : TM;
     bf16x8 af[2][TM], bfr[2][TN];
     // fragments are read in the order of their first use by the MFMA sequence (i outer, j inner):
@@ -420,7 +437,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
     } while (0)
 
     // every kernel argument the epilogue needs is in registers before the loop (see the file header)
-    asm volatile("" ::"s"(Cout), "s"(M), "s"(N), "s"(rope.table), "s"(rope.pos), "s"(rope.L), "s"(rope.rope_cols));
+    asm volatile("" ::"s"(Cout), "s"(M), "s"(N), "s"(rope.table), "s"(rope.pos), "s"(rope.L), "s"(rope.rope_cols),
+                 "s"(rope.c_panel_rows));
 
 #pragma unroll
     for (int s = 0; s < P; ++s)
@@ -434,6 +452,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
 #pragma unroll
     for (int r = 0; r < NRD; ++r) DLLM_READ(r, smem, lhalf ^ sw, 0);
 
+    // The K loop exists twice: SKIP = false multiplies every sub-tile, with no branch between the MFMAs
+    // (every workgroup but those of a ragged last row tile); SKIP = true tests each MFMA's sub-tile.
+    auto k_loop = [&](auto skip_tag) __attribute__((always_inline)) {
+    constexpr bool SKIP = decltype(skip_tag)::value;
     int slot = 0, cslot = P % NST;  // slot of stage kt; slot that receives stage kt + P
     int kt = 0;
 #pragma unroll
@@ -459,15 +481,25 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
                     asm volatile("" ::: "memory");
                 }
                 const int c0 = kk * LOADS / KS, c1 = (kk + 1) * LOADS / KS, NC = c1 - c0;
+                // The substep in front of the barrier ends with a wait for every fragment read it issued, so
+                // it issues them during its first MFMAs (the rest of its MFMAs then cover their latency) and
+                // its copies during the later ones; the other substeps spread both evenly.
+                const bool front = kEarlyReads && kk == KS - 2;
+                constexpr int HALF = (NMF + 1) / 2, RQ = (NRD + HALF - 1) / HALF, REST = NMF - HALF, RDIV = REST > 0 ? REST : 1;
 #pragma unroll
                 for (int m = 0; m < NMF; ++m) {
+                    const int r0 = front ? min(NRD, m * RQ) : m * NRD / NMF;
+                    const int r1 = front ? min(NRD, (m + 1) * RQ) : (m + 1) * NRD / NMF;
 #pragma unroll
-                    for (int r = m * NRD / NMF; r < (m + 1) * NRD / NMF; ++r) DLLM_READ(r, rs, ch, nxt);
+                    for (int r = r0; r < r1; ++r) DLLM_READ(r, rs, ch, nxt);
                     if (phase == 0) {
+                        const bool late = front && REST > 0;
+                        const int q0 = late ? (m < HALF ? 0 : (m - HALF) * NC / RDIV) : m * NC / NMF;
+                        const int q1 = late ? (m < HALF ? 0 : (m - HALF + 1) * NC / RDIV) : (m + 1) * NC / NMF;
 #pragma unroll
-                        for (int c = c0 + m * NC / NMF; c < c0 + (m + 1) * NC / NMF; ++c) DLLM_COPY(c, kt + P, cslot);
+                        for (int c = c0 + q0; c < c0 + q1; ++c) DLLM_COPY(c, kt + P, cslot);
                     }
-                    if (!kSkipEmpty || m / TN < tm_valid)
+                    if (!SKIP || m / TN < tm_valid)
                         acc[m / TN][m % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][m % TN], af[cur][m / TN],
                                                                                      acc[m / TN][m % TN], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);  // keeps the hand-made interleaving
@@ -477,6 +509,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
             cslot = cslot + 1 == NST ? 0 : cslot + 1;
         }
     }
+    };
+    if (kSkipEmpty && tm_valid < TM) k_loop(std::true_type{});
+    else k_loop(std::false_type{});
 #undef DLLM_COPY
 #undef DLLM_READ
     const int n_lim = epi_paired(EPI) ? N / 2 : N;
@@ -729,9 +764,23 @@ Plan make_plan(int epi, int M, int N, int K, int split_limit = kGemmMaxSplits)
     return p;
 }
 
+// Pitches of the kernel's operand addressing for a layout (see the kernel); false if a panel-major operand
+// is asked of a kernel that cannot read it or does not fit 32-bit offsets.
+bool set_layout(RopeArgs &r, const GemmLayout &lay, bool fast, int K)
+{
+    if (!fast && (lay.a_panel_rows || lay.w_panel_rows || lay.c_panel_rows)) return false;
+    if ((double)lay.a_panel_rows * 64 * 2 >= 4.0e9 || (double)lay.w_panel_rows * 64 * 2 >= 4.0e9) return false;
+    r.a_row_pitch = lay.a_panel_rows ? 64u : (uint32_t)K * 2u;
+    r.a_panel_pitch = lay.a_panel_rows ? (uint32_t)lay.a_panel_rows * 64u : 64u;
+    r.w_row_pitch = lay.w_panel_rows ? 64u : (uint32_t)K * 2u;
+    r.w_panel_pitch = lay.w_panel_rows ? (uint32_t)lay.w_panel_rows * 64u : 64u;
+    r.c_panel_rows = lay.c_panel_rows;
+    return true;
+}
+
 template <int BM, int BN, int WM, int WN, int BK, int NST, int EPI>
 hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *W, void *C, int M, int N, int K,
-                      int splits, RopeArgs rope = RopeArgs{nullptr, nullptr, {1}, {0}})
+                      int splits, RopeArgs rope)
 {
     constexpr int BN_OUT = epi_paired(EPI) ? BN / 2 : BN;
     const int n_lim = epi_paired(EPI) ? N / 2 : N;
@@ -763,8 +812,9 @@ hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *
 
 template <int EPI>
 hipError_t dispatch(hipStream_t stream, Plan p, const void *A, const void *W, void *C, int M, int N, int K,
-                    RopeArgs rope = RopeArgs{nullptr, nullptr, {1}, {0}})
+                    const GemmLayout &lay, RopeArgs rope = RopeArgs{nullptr, nullptr, {1}, {0}, 0, 0, 0, 0, 0})
 {
+    if (!set_layout(rope, lay, p.fast, K)) return hipErrorInvalidValue;
     switch (p.cfg) {
     case 0:
         if constexpr (EPI != kEpiPartial)
@@ -806,38 +856,66 @@ bool gemm_qkv_rope_supported(int M, int d, int dh)
 }
 
 hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
-                                const float2 *table, int L, const int32_t *pos)
+                                const float2 *table, int L, const int32_t *pos, const GemmLayout &lay)
 {
-    const RopeArgs rope{table, pos, {L}, {2 * d}};
+    const RopeArgs rope{table, pos, {L}, {2 * d}, 0, 0, 0, 0, 0};
     const Plan p = make_plan(dh == 128 ? kEpiRope128 : kEpiRope64, M, 3 * d, d);
-    if (dh == 128) return dispatch<kEpiRope128>(stream, p, A, W, C, M, 3 * d, d, rope);
-    return dispatch<kEpiRope64>(stream, p, A, W, C, M, 3 * d, d, rope);
+    if (dh == 128) return dispatch<kEpiRope128>(stream, p, A, W, C, M, 3 * d, d, lay, rope);
+    return dispatch<kEpiRope64>(stream, p, A, W, C, M, 3 * d, d, lay, rope);
 }
 
 size_t gemm_rowstats_max_parts(int N) { return (size_t)(N + 63) / 64 + 1; }
 
 hipError_t launch_gemm_rowstats(hipStream_t stream, const void *A, const void *W, float *stats, int M, int N, int K,
-                                int mask_id, int *parts)
+                                int mask_id, int *parts, const GemmLayout &lay)
 {
     const Plan p = make_plan(kEpiRowStats, M, N, K);
     const TileCfg &t = kCfg[p.cfg];
     *parts = (N + t.bn - 1) / t.bn * t.wn;
     if ((size_t)*parts > gemm_rowstats_max_parts(N)) return hipErrorInvalidValue;
-    RopeArgs ea{nullptr, nullptr, {0}, {0}};
+    RopeArgs ea{nullptr, nullptr, {0}, {0}, 0, 0, 0, 0, 0};
     ea.parts = *parts;
     ea.mask_id = mask_id;
-    return dispatch<kEpiRowStats>(stream, p, A, W, stats, M, N, K, ea);
+    return dispatch<kEpiRowStats>(stream, p, A, W, stats, M, N, K, lay, ea);
 }
 
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
-                       int K, int split_limit)
+                       int K, int split_limit, const GemmLayout &lay)
 {
     const Plan p = make_plan(epi, M, N, K, split_limit);
     switch (epi) {
-    case kEpiBf16: return dispatch<kEpiBf16>(stream, p, A, W, C, M, N, K);
-    case kEpiSwiglu: return dispatch<kEpiSwiglu>(stream, p, A, W, C, M, N, K);
-    default: return dispatch<kEpiPartial>(stream, p, A, W, C, M, N, K);
+    case kEpiBf16: return dispatch<kEpiBf16>(stream, p, A, W, C, M, N, K, lay);
+    case kEpiSwiglu: return dispatch<kEpiSwiglu>(stream, p, A, W, C, M, N, K, lay);
+    default: return dispatch<kEpiPartial>(stream, p, A, W, C, M, N, K, lay);
     }
+}
+
+bool gemm_async_copy_path(int epi, int M, int N, int K, int split_limit)
+{
+    return make_plan(epi, M, N, K, split_limit).fast;
+}
+
+namespace {
+// dst[K / 32][rows][32] = src[rows][K], 16 bytes per thread; K % 32 == 0
+__global__ __launch_bounds__(256) void pack_panels_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                          size_t rows, int chunks_per_row)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * chunks_per_row) return;
+    const size_t r = idx / chunks_per_row;
+    const int c = (int)(idx - r * chunks_per_row);
+    dst[((size_t)(c >> 2) * rows + r) * 4 + (c & 3)] = src[idx];
+}
+}  // namespace
+
+hipError_t launch_pack_panels(hipStream_t stream, const void *src, void *dst, size_t rows, int K)
+{
+    if (K % 32 || rows == 0) return hipErrorInvalidValue;
+    const size_t n = rows * (size_t)(K / 8);
+    if ((n + 255) / 256 > 0x7fffffffull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(pack_panels_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, (const uint4 *)src,
+                       (uint4 *)dst, rows, K / 8);
+    return hipGetLastError();
 }
 
 }  // namespace dllm

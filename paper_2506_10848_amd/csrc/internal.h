@@ -43,25 +43,45 @@ hipError_t launch_embed(hipStream_t stream, const int32_t *tokens, const int32_t
                         int M, int d, int vocab, int32_t *bad_token);
 // dst[rows[r]][d .. 3d) = src[r][d .. 3d): the k and v thirds of recomputed rows go to their cache rows
 hipError_t launch_scatter_kv(hipStream_t stream, const void *src, void *dst, const int32_t *rows, int n_rows, int d);
+// h_panel_rows != 0: h is written panel-major (see GemmLayout) with that many rows per panel (>= M; d % 32 == 0)
 hipError_t launch_add_rmsnorm(hipStream_t stream, float *x, const float *partials, int n_partials, const void *gain,
-                              void *h, int M, int d, float eps);
+                              void *h, int M, int d, float eps, int h_panel_rows = 0);
 hipError_t launch_rope_table(hipStream_t stream, float2 *table, int max_pos, int dh, float theta);
 // table may be null: angles are then computed in the kernel (slow; test hook)
 hipError_t launch_rope(hipStream_t stream, void *qkv, const float2 *table, int B, int L, int H, int dh, float theta);
-hipError_t launch_attention(hipStream_t stream, const void *qkv, void *out, int B, int L, int H, int dh);
+// out_panel_rows != 0 (here and in launch_attention_rows): out is written panel-major (see GemmLayout)
+hipError_t launch_attention(hipStream_t stream, const void *qkv, void *out, int B, int L, int H, int dh,
+                            int out_panel_rows = 0);
 // Queries of sequence b are the rows [first[b], first[b] + count[b]) of q (row stride 3d, q third);
 // it attends to the Lk rows of kv that start at row b * Lk (k and v thirds); out rows as q rows.
 struct SeqRows {
     int first[DLLM_MAX_BATCH], count[DLLM_MAX_BATCH];
 };
 hipError_t launch_attention_rows(hipStream_t stream, const void *q, const void *kv, void *out, int B, int Lk, int H,
-                                 int dh, const SeqRows &rows);
+                                 int dh, const SeqRows &rows, int out_panel_rows = 0);
 
 enum GemmEpilogue {
     kEpiBf16 = 0,     // C bf16 [M][N]
     kEpiSwiglu = 1,   // W = [gate | up] rows; C bf16 [M][N/2] = silu(gate) * up
     kEpiPartial = 2,  // C fp32 [splits][M][N], one slab per K split
 };
+// Layout of a product's operands and (SwiGLU only) of its output.  Row-major is the default.  Panel-major:
+// a matrix X[rows][K] stored as [K / 32][panel_rows][32], i.e. panel p holds elements [32 p, 32 p + 32) of
+// every row, rows contiguous (64 bytes each); the rows a product uses may be a range of the panel's rows
+// (the operand pointer then points at the first of them inside panel 0).  A tile's K-stage is then one
+// contiguous block in memory and every request to the L2 is a whole 128-byte line: measured on MI355X,
+// the asynchronous tile copies reach 115 GB/s per CU from panel-major operands against 65 GB/s from
+// row-major ones when the lines come from the L2, and 6.3 against 4.4 TB/s when they come from HBM.
+// Only the asynchronous-copy kernel (K % 64 == 0, see gemm_async_copy_path) reads panel-major operands.
+struct GemmLayout {
+    int a_panel_rows = 0;  // 0: A row-major [M][K]; else rows per panel of a panel-major A
+    int w_panel_rows = 0;  // 0: W row-major [N][K]; else rows per panel of a panel-major W (all N rows)
+    int c_panel_rows = 0;  // kEpiSwiglu only: 0: output row-major [M][N/2]; else rows per panel of the output
+};
+// Whether the product will run on the asynchronous-copy kernel (the one that takes panel-major operands).
+bool gemm_async_copy_path(int epi, int M, int N, int K, int split_limit = 8);
+// dst[K / 32][rows][32] (panel-major) = src[rows][K]; K % 32 == 0.
+hipError_t launch_pack_panels(hipStream_t stream, const void *src, void *dst, size_t rows, int K);
 // How many K splits launch_gemm will use for a kEpiPartial problem: between 1 and min(split_limit,
 // kGemmMaxSplits).  The caller derives split_limit from the slab space it has and passes the same value
 // to launch_gemm, so a plan never asks for more slabs than exist.
@@ -82,16 +102,17 @@ void gemm_reload_env();
 bool gemm_qkv_rope_supported(int M, int d, int dh);
 // pos (nullable): position of every row; default row % L.
 hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
-                                const float2 *table, int L, const int32_t *pos = nullptr);
+                                const float2 *table, int L, const int32_t *pos = nullptr,
+                                const GemmLayout &lay = GemmLayout());
 // C = A[M][K] * W[N][K]^T.  For kEpiSwiglu N counts gate + up rows.
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
-                       int K, int split_limit = kGemmMaxSplits);
+                       int K, int split_limit = kGemmMaxSplits, const GemmLayout &lay = GemmLayout());
 // The same product with the greedy decode fused in: no C; per row and per column slice (a wave's
 // share of a tile, *parts of them) the maximum of the bf16-rounded values, the sum of
 // exp(x - max) and the lowest column holding the maximum, column mask_id left out.
 // stats: fp32/int32 planes [3][*parts][M]; *parts <= gemm_rowstats_max_parts(N).
 size_t gemm_rowstats_max_parts(int N);
 hipError_t launch_gemm_rowstats(hipStream_t stream, const void *A, const void *W, float *stats, int M, int N, int K,
-                                int mask_id, int *parts);
+                                int mask_id, int *parts, const GemmLayout &lay = GemmLayout());
 
 }  // namespace dllm

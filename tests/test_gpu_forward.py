@@ -63,11 +63,11 @@ GEMM_SHAPES = [  # M, N, K
 def test_linear(M, N, K, tile, fallback, monkeypatch):
     """Every tile shape, through the asynchronous-copy kernel (K % 64 == 0) and
     through the register-staged kernel (forced, or picked for a ragged K)."""
-    b = binding()
     if tile >= 0:
         monkeypatch.setenv("DLLM_GEMM_CFG", str(tile))
     if fallback:
         monkeypatch.setenv("DLLM_GEMM_FALLBACK", "1")
+    b = binding()                  # (re-reads the switches just set)
     A = rand_bf16((M, K), 1.0, 11, f"A{M}{K}")
     W = rand_bf16((N, K), 0.05, 12, f"W{N}{K}")
     got = f64(b.op_linear(A.to(DEV), W.to(DEV)))
@@ -79,17 +79,74 @@ def test_linear(M, N, K, tile, fallback, monkeypatch):
 @pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("fallback", [0, 1])
 def test_linear_swiglu(M, f, K, tile, fallback, monkeypatch):
-    b = binding()
     if tile >= 0:
         monkeypatch.setenv("DLLM_GEMM_CFG", str(tile))
     if fallback:
         monkeypatch.setenv("DLLM_GEMM_FALLBACK", "1")
+    b = binding()                  # (re-reads the switches just set)
     A = rand_bf16((M, K), 1.0, 21, f"A{M}{K}")
     W = rand_bf16((2 * f, K), 0.08, 22, f"W{f}{K}")
     got = f64(b.op_linear_swiglu(A.to(DEV), W.to(DEV)))
     gu = oracle.linear(f64(A), bits(W))
     ref = oracle.swiglu(gu[:, :f], gu[:, f:])
     close_bf16(got, ref)
+
+
+def unpack_panels(t, rows):
+    """panel-major [K/32, panel_rows, 32] -> row-major [rows, K] (the first `rows` rows of every panel)."""
+    return t[:, :rows].permute(1, 0, 2).reshape(rows, -1)
+
+
+@pytest.mark.parametrize("M,N,K", [(96, 768, 256), (300, 520, 1024), (512, 1024, 512), (1400, 1100, 128), (70, 64, 64)])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("a_pk,w_pk", [(True, True), (True, False), (False, True)])
+def test_linear_panel_major_operands(M, N, K, tile, a_pk, w_pk, monkeypatch):
+    """The same product from panel-major operands ([K/32][rows][32], the layout a step keeps its
+    activations and weight copies in), every tile shape: A with more rows per panel than the product
+    uses and a row offset into the panel, as the vocabulary projection of a window reads it."""
+    if tile >= 0:
+        monkeypatch.setenv("DLLM_GEMM_CFG", str(tile))
+    b = binding()                  # (re-reads the switch just set)
+    A = rand_bf16((M + 37, K), 1.0, 11, f"A{M}{K}")        # rows 21 .. 21 + M are the operand
+    W = rand_bf16((N, K), 0.05, 12, f"W{N}{K}")
+    Ad, Wd = A.to(DEV), W.to(DEV)
+    Ap = b.op_pack_panels(Ad)
+    assert torch.equal(unpack_panels(Ap, M + 37), Ad)       # the packing itself
+    a_arg = Ap.view(-1)[21 * 32:] if a_pk else Ad[21:21 + M].contiguous()
+    got = f64(b.op_linear_panels(a_arg, b.op_pack_panels(Wd) if w_pk else Wd, M, N, K, False,
+                                 M + 37 if a_pk else 0, w_pk, 0))
+    ref = oracle.linear(f64(A[21:21 + M]), bits(W))
+    close_bf16(got, ref)
+    # and bit-identical to the row-major run (same kernel, same order of accumulation)
+    assert torch.equal(b.op_linear_panels(a_arg, b.op_pack_panels(Wd) if w_pk else Wd, M, N, K, False,
+                                          M + 37 if a_pk else 0, w_pk, 0), b.op_linear(Ad[21:21 + M].contiguous(), Wd))
+
+
+@pytest.mark.parametrize("M,f,K", [(96, 704, 256), (130, 192, 128), (512, 1408, 512)])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4])
+def test_linear_swiglu_panel_major_output(M, f, K, tile, monkeypatch):
+    """Gate/up projection + SwiGLU from panel-major operands into a panel-major output (what the down
+    projection then reads)."""
+    if tile >= 0:
+        monkeypatch.setenv("DLLM_GEMM_CFG", str(tile))
+    b = binding()                  # (re-reads the switch just set)
+    A = rand_bf16((M, K), 1.0, 21, f"A{M}{K}")
+    W = rand_bf16((2 * f, K), 0.08, 22, f"W{f}{K}")
+    out = b.op_linear_panels(b.op_pack_panels(A.to(DEV)).view(-1), b.op_pack_panels(W.to(DEV)), M, 2 * f, K, True, M, True, M + 5)
+    got = unpack_panels(out, M)
+    gu = oracle.linear(f64(A), bits(W))
+    close_bf16(f64(got), oracle.swiglu(gu[:, :f], gu[:, f:]))
+    assert torch.equal(got, b.op_linear_swiglu(A.to(DEV), W.to(DEV)))
+    assert not out[:, M:].any()                              # rows past M of the panels stay untouched
+
+
+def test_panel_major_operands_are_refused_where_no_kernel_reads_them():
+    b = binding()
+    A = torch.zeros((64, 72), dtype=torch.bfloat16, device=DEV)           # K = 72: register-staged kernel only
+    W = torch.zeros((64, 72), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(b.DllmError) as e:
+        b.op_linear_panels(A, W, 64, 64, 72, False, 64, True, 0)
+    assert e.value.code == b.EINVAL
 
 
 def test_linear_full_size_sampled():
@@ -147,9 +204,9 @@ def test_rope(B, L, H, dh, theta):
 def test_linear_qkv_rope(B, L, H, dh, theta, tile, monkeypatch):
     """QKV projection with the rotary embedding in its epilogue, every tile shape that has it:
     the rotation acts on the fp32 accumulators, so the reference rotates the unrounded product."""
-    b = binding()
     if tile >= 0:
         monkeypatch.setenv("DLLM_GEMM_CFG", str(tile))
+    b = binding()                  # (re-reads the switch just set)
     d = H * dh
     A = rand_bf16((B * L, d), 1.0, 52, f"A{d}")
     W = rand_bf16((3 * d, d), 0.05, 53, f"Wqkv{d}")
@@ -237,6 +294,14 @@ def test_forward_tiny_config_unfused_rope_and_fallback_gemm(monkeypatch):
     monkeypatch.setenv("DLLM_GEMM_FALLBACK", "1")
     got, ref = run_forward(cfg, 2)
     logits_close(got, ref)
+
+
+def test_forward_without_panel_major_weight_copies(monkeypatch):
+    """DLLM_NO_PACK: the handle keeps no panel-major copies and every product reads row-major operands."""
+    monkeypatch.setenv("DLLM_NO_PACK", "1")
+    for name, batch in (("tiny", 2), ("medium", 1)):
+        got, ref = run_forward(synth.CONFIGS[name], batch)
+        logits_close(got, ref)
 
 
 def test_forward_tiny_config_wide_init_batch3():
