@@ -637,11 +637,14 @@ struct TileCfg {
     int bm, bn, bk, nst, wn;  // wn: wave columns of the tile
     float step_us, epi_us;
 };
-constexpr int kNumCfg = 7;
+constexpr int kNumCfg = 10;
 const TileCfg kCfg[kNumCfg] = {
     {256, 256, 32, 4, 2, 1.70f, 9.0f}, {256, 192, 32, 5, 2, 1.45f, 8.0f}, {256, 128, 64, 3, 2, 0.97f, 6.0f},
     {256, 96, 64, 3, 1, 0.77f, 5.0f},  {128, 128, 64, 4, 2, 0.62f, 3.5f}, {128, 64, 64, 4, 2, 1.00f, 2.5f},
     {64, 64, 64, 8, 2, 0.30f, 1.5f},  // few rows (cached steps): a deep ring keeps 56 KB of weights in flight per workgroup
+    // 32-deep stages with deep rings: with panel-major operands a 64-byte row piece is as cheap a request as a
+    // 128-byte one, and the ring then looks further ahead in time
+    {128, 192, 32, 7, 2, 0.72f, 5.0f}, {256, 128, 32, 6, 2, 1.00f, 6.0f}, {128, 128, 32, 8, 2, 0.66f, 3.5f},
 };
 constexpr int kNumCU = 256;
 constexpr int kLdsPerCU = 160 * 1024;
@@ -825,7 +828,10 @@ hipError_t dispatch(hipStream_t stream, Plan p, const void *A, const void *W, vo
     case 3: return launch_cfg<256, 96, 4, 1, 64, 3, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
     case 4: return launch_cfg<128, 128, 2, 2, 64, 4, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
     case 5: return launch_cfg<128, 64, 2, 2, 64, 4, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
-    default: return launch_cfg<64, 64, 2, 2, 64, 8, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
+    case 6: return launch_cfg<64, 64, 2, 2, 64, 8, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
+    case 7: return launch_cfg<128, 192, 2, 2, 32, 7, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
+    case 8: return launch_cfg<256, 128, 2, 2, 32, 6, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
+    default: return launch_cfg<128, 128, 2, 2, 32, 8, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
     }
 }
 

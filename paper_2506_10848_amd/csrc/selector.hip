@@ -226,7 +226,7 @@ __global__ __launch_bounds__(kSeqThreads) void seq_phase_kernel(int L, int32_t *
 {
     extern __shared__ unsigned long long keys[];          // [L] (confidence bits, ~position) of candidates
     uint8_t *flag = reinterpret_cast<uint8_t *>(keys + L);  // [L] 1 = commit
-    __shared__ int s_ecand, s_first, s_nhigh, s_ncand, s_nmask;
+    __shared__ int s_ecand, s_first, s_nhigh, s_ncand, s_nmask, s_count;
     __shared__ unsigned long long s_best;
     __shared__ int wave_tot[kSeqThreads / kWave];
 
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(kSeqThreads) void seq_phase_kernel(int L, int32_t *
             atomicMax(&s_best, best);
             __syncthreads();
             if (tid == 0) flag[0xffffffffu - (unsigned)s_best] = 1;
-        } else {
+        } else if (ncand <= 1024) {
             // rank by counting: keys are distinct, so exactly top_k ranks fall below top_k
             for (int idx = tid; idx < ncand; idx += kSeqThreads) {
                 const unsigned long long key = keys[idx];
@@ -279,6 +279,23 @@ __global__ __launch_bounds__(kSeqThreads) void seq_phase_kernel(int L, int32_t *
                 for (int j = 0; j < ncand; ++j) rank += keys[j] > key;
                 if (rank < w.top_k) flag[0xffffffffu - (unsigned)key] = 1;
             }
+        } else {
+            // many candidates: the top_k-th largest key, bit by bit from the top (the largest value t such
+            // that at least top_k keys are >= t); 64 counting passes over the keys instead of ncand per key
+            unsigned long long t = 0ull;
+            for (int bit = 63; bit >= 0; --bit) {
+                const unsigned long long cand = t | (1ull << bit);
+                if (tid == 0) s_count = 0;
+                __syncthreads();
+                int mine = 0;
+                for (int idx = tid; idx < ncand; idx += kSeqThreads) mine += keys[idx] >= cand;
+                if (mine) atomicAdd(&s_count, mine);
+                __syncthreads();
+                if (s_count >= w.top_k) t = cand;   // uniform over the workgroup
+                __syncthreads();
+            }
+            for (int idx = tid; idx < ncand; idx += kSeqThreads)
+                if (keys[idx] >= t) flag[0xffffffffu - (unsigned)keys[idx]] = 1;
         }
     }
     __syncthreads();

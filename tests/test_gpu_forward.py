@@ -58,7 +58,7 @@ GEMM_SHAPES = [  # M, N, K
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
 @pytest.mark.parametrize("fallback", [0, 1])
 def test_linear(M, N, K, tile, fallback, monkeypatch):
     """Every tile shape, through the asynchronous-copy kernel (K % 64 == 0) and
@@ -76,7 +76,7 @@ def test_linear(M, N, K, tile, fallback, monkeypatch):
 
 
 @pytest.mark.parametrize("M,f,K", [(96, 688, 256), (130, 200, 128), (512, 1408, 512)])
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
 @pytest.mark.parametrize("fallback", [0, 1])
 def test_linear_swiglu(M, f, K, tile, fallback, monkeypatch):
     if tile >= 0:
@@ -98,7 +98,7 @@ def unpack_panels(t, rows):
 
 
 @pytest.mark.parametrize("M,N,K", [(96, 768, 256), (300, 520, 1024), (512, 1024, 512), (1400, 1100, 128), (70, 64, 64)])
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
 @pytest.mark.parametrize("a_pk,w_pk", [(True, True), (True, False), (False, True)])
 def test_linear_panel_major_operands(M, N, K, tile, a_pk, w_pk, monkeypatch):
     """The same product from panel-major operands ([K/32][rows][32], the layout a step keeps its
@@ -123,7 +123,7 @@ def test_linear_panel_major_operands(M, N, K, tile, a_pk, w_pk, monkeypatch):
 
 
 @pytest.mark.parametrize("M,f,K", [(96, 704, 256), (130, 192, 128), (512, 1408, 512)])
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 7, 8, 9])
 def test_linear_swiglu_panel_major_output(M, f, K, tile, monkeypatch):
     """Gate/up projection + SwiGLU from panel-major operands into a panel-major output (what the down
     projection then reads)."""
@@ -200,7 +200,7 @@ def test_rope(B, L, H, dh, theta):
 
 
 @pytest.mark.parametrize("B,L,H,dh,theta", [(1, 96, 4, 64, 1e4), (2, 70, 3, 128, 5e5), (1, 300, 5, 128, 5e5)])
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
 def test_linear_qkv_rope(B, L, H, dh, theta, tile, monkeypatch):
     """QKV projection with the rotary embedding in its epilogue, every tile shape that has it:
     the rotation acts on the fp32 accumulators, so the reference rotates the unrounded product."""

@@ -223,6 +223,22 @@ def test_long_sequence_and_many_commits():
         run_case(B, L, V, mask_id, logits, mask.clone(), prev.clone(), sps)
 
 
+def test_top_k_among_thousands_of_candidates():
+    """The longest sequence the library takes, every position masked: top-k with 1 < k < candidates over
+    more than 1024 candidates goes through the bit-by-bit selection of the k-th largest key."""
+    B, L, V = 2, 8192, 64
+    logits, mask, prev, mask_id = make_inputs("selector", B, L, V, seed_shift=13)     # confidences spread over (0, 1)
+    mask[:] = 1
+    total_amb = 0
+    for stage, lo, hi, k, tau_high in [(sf.SLOW, 0, L - 1, 32, 0.9), (sf.SLOW, 5, L - 1, 1500, 0.9),
+                                       (sf.FAST, 100, 7000, 200, 2.0), (sf.SLOW, 0, L - 1, 8191, 0.9)]:
+        sps = [sf.StageParams(stage, lo, hi, k, -1.0, tau_high, 0, 0, L) for _ in range(B)]
+        amb, res = run_case(B, L, V, mask_id, logits, mask.clone(), prev.clone(), sps)
+        total_amb += amb
+        assert all(len(r[0]) == k for r in res)
+    assert total_amb <= 4          # of 8 decisions; the rest were compared position by position
+
+
 def test_error_paths_reach_the_caller():
     b = binding()
     B, L, V = 1, 8, 64

@@ -660,7 +660,7 @@ def test_decode_low_confidence(n_steps_div, n_blocks):
 
 # ---- greedy decode fused into the vocabulary projection ----------------------------
 
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, "fallback"])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 7, 8, 9, "fallback"])
 @pytest.mark.parametrize("cfg_name,n_layers,batch,stage", [("tiny", 2, 3, "slow"), ("tiny", 2, 3, "fast"),
                                                            ("medium", 2, 2, "fast"), ("llada8b", 1, 1, "slow"),
                                                            # vocabulary that ends inside an MFMA tile, [MASK] mid-tile
