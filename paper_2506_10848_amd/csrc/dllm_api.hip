@@ -26,6 +26,10 @@ struct Workspace {
     uint16_t *act = nullptr;     // [M][f]
     float *partials = nullptr;   // split-K slabs fp32 [splits][rows][d], partials_cap floats
     size_t partials_cap = 0;
+    float *ssq = nullptr;        // per row, partial sums of squares of the residual stream: [M][ssq_stride]
+    int ssq_stride = 0;
+    int32_t *tickets = nullptr;  // one counter per output tile of a split-K residual product, zero between launches
+    int n_tickets = 0;
     uint16_t *logits = nullptr;  // [M][V]
     float *rowstats = nullptr;   // [3][gemm_rowstats_max_parts(V)][M]: per-slice (max, sum of exp, argmax) of the fused selector
     int32_t *pred = nullptr;     // [M]
@@ -69,6 +73,8 @@ struct dllm_handle {
     std::string err;
     int last_B = 0, last_L = 0;
     bool fused_selector = true;  // dllm_set_fused_selector
+    bool fused_norm = true;      // RMSNorm folded into the projections (off: environment DLLM_NO_FUSED_NORM at create)
+    bool fused_splitk = false;   // also where the O / down projection runs K splits (environment DLLM_FUSED_SPLITK)
     // measurement hook: event pairs around the gate/up GEMM launches
     std::vector<hipEvent_t> prof_ev;
     int prof_cap = 0, prof_used = 0;
@@ -185,8 +191,9 @@ int check_commit_list(dllm_handle *h, const dllm_commit_list *o, CommitOut *c)
 // kernel turns them into ws.pred / ws.conf at the masked rows of the windows.
 // h_panel_rows: 0, or the rows per panel of a panel-major ws.h.
 int vocab_rows(dllm_handle *h, long h_row, long abs_row, int n, int L, const uint8_t *mask, const SelectArgs *win,
-               int h_panel_rows)
+               int h_panel_rows, RowScale scale)
 {
+    if (scale.ssq) scale.ssq += h_row * scale.stride;
     const dllm_config &c = h->cfg;
     Workspace &w = h->ws;
     // the first of the n rows: 64 bytes per row inside panel 0, or d_model elements per row
@@ -195,12 +202,12 @@ int vocab_rows(dllm_handle *h, long h_row, long abs_row, int n, int L, const uin
     const GemmLayout lay{h_panel_rows, h_panel_rows ? c.vocab : 0, 0};
     if (h->fused_selector && mask && win) {
         int parts = 0;
-        HIP_TRY(h, launch_gemm_rowstats(h->stream, A, W, w.rowstats, n, c.vocab, c.d_model, c.mask_id, &parts, lay));
+        HIP_TRY(h, launch_gemm_rowstats(h->stream, A, W, w.rowstats, n, c.vocab, c.d_model, c.mask_id, &parts, lay, scale));
         HIP_TRY(h, launch_rowstats_merge(h->stream, w.rowstats, parts, n, (int)abs_row, L, mask, *win, w.pred, w.conf));
     } else {
         if (int rc = ensure_logits(h)) return rc;
         HIP_TRY(h, launch_gemm(h->stream, kEpiBf16, A, W, w.logits + abs_row * (long)c.vocab, n, c.vocab, c.d_model,
-                               kGemmMaxSplits, lay));
+                               kGemmMaxSplits, lay, scale));
     }
     return DLLM_OK;
 }
@@ -223,48 +230,108 @@ PanelChoice pick_panels(const dllm_handle *h, int rows)
     return PanelChoice{pd ? rows : 0, pf ? rows : 0};
 }
 
+// Embedding, all layers and the final norm over `rows` rows (all B * L of them, or the gathered subset of a
+// cached step), leaving in ws.h what the vocabulary projection multiplies.
+//   rows_d / pos_d (device, nullable): batch row and position of every row of a gathered subset
+//   kv_rows (nullable): cached step: queries of sequence b are rows [first, first + count) and attend to the
+//                       layer's key/value cache; to_cache: the QKV projection writes straight into the cache
+// The RMSNorm in front of a projection is applied in one of two ways, chosen per product.  Folded: whoever
+// produced the residual stream left bf16(x * gain) and per-row partial sums of squares, and the projection
+// scales its output rows (*scale / sc say how).  Separate: ws.h holds normalised rows and sc is empty.
+// The embedding kernel always leaves the folded form.  An O or down projection that the planner runs
+// without K splits adds the residual and leaves the folded form in its own epilogue; with K splits it leaves
+// fp32 slabs and the residual-add + RMSNorm kernel sums them into the separate form (summing them inside the
+// projection, by the last workgroup of each tile to arrive, is built and tested, environment
+// DLLM_FUSED_SPLITK=1, but measured slower: 93 vs 54 + 10.7 us for the down projection at M = 512, the
+// device-scope release / acquire around the tickets costs more than the kernel it saves).
+struct LayerRun {
+    int rows, B, L;
+    const int32_t *rows_d = nullptr, *pos_d = nullptr;
+    const SeqRows *kv_rows = nullptr;
+    bool to_cache = false;
+};
+int run_layers(dllm_handle *h, const int32_t *tokens, const LayerRun &r, int *h_panel_rows, RowScale *scale)
+{
+    const dllm_config &c = h->cfg;
+    const int M = r.rows, d = c.d_model, f = c.d_ffn;
+    Workspace &w = h->ws;
+    hipStream_t st = h->stream;
+    const int slabs = slab_limit(h, M);
+    if (slabs < 1) return fail(h, DLLM_ESTATE, "the split-K workspace does not hold one slab of %d rows", M);
+    const PanelChoice pc = pick_panels(h, M);
+    const int pd = pc.d_rows, pf = pc.f_rows;
+    const bool fused = h->fused_norm;
+    const bool fused_rope = gemm_qkv_rope_supported(M, d, c.head_dim);
+    *h_panel_rows = pd;
+    RowScale sc;  // how the rows currently in ws.h still have to be scaled (empty: they are normalised)
+    const void *first_gain = c.n_layers > 0 ? h->attn_norm[0] : h->final_norm;
+    if (fused) {
+        HIP_TRY(h, launch_embed(st, tokens, r.rows_d, h->embed, w.x, M, d, c.vocab, w.bad_token, first_gain, w.h, pd, w.ssq,
+                                w.ssq_stride));
+        sc = RowScale{w.ssq, 1, w.ssq_stride, c.rms_eps};
+    } else {
+        HIP_TRY(h, launch_embed(st, tokens, r.rows_d, h->embed, w.x, M, d, c.vocab, w.bad_token));
+        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, 0, first_gain, w.h, M, d, c.rms_eps, pd));
+    }
+    ResidualOut ro;
+    ro.x = w.x; ro.h = w.h; ro.h_panel_rows = pd; ro.ssq = w.ssq; ro.ssq_stride = w.ssq_stride; ro.slabs = w.partials;
+    ro.tickets = w.tickets; ro.n_tickets = w.n_tickets;
+    // x += A W^T and the operand of the next projection (whose norm has gain `gain`), one way or the other
+    auto residual_product = [&](const void *A, const void *W, int K, const GemmLayout &lay, const void *gain) -> int {
+        const int splits = gemm_num_splits(M, d, K, slabs);
+        if (fused && (splits == 1 || h->fused_splitk)) {
+            ro.gain = gain;
+            sc = RowScale{w.ssq, 0, w.ssq_stride, c.rms_eps};
+            HIP_TRY(h, launch_gemm_residual(st, A, W, ro, M, d, K, h->fused_splitk ? slabs : 1, lay, &sc.parts));
+        } else {
+            HIP_TRY(h, launch_gemm(st, kEpiPartial, A, W, w.partials, M, d, K, slabs, lay));
+            HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, splits, gain, w.h, M, d, c.rms_eps, pd));
+            sc = RowScale();
+        }
+        return DLLM_OK;
+    };
+    for (int l = 0; l < c.n_layers; ++l) {
+        const void *wqkv = pd ? h->wqkv_p[l] : h->wqkv[l];
+        const GemmLayout lq{pd, pd ? 3 * d : 0, 0};
+        void *qkv_out = r.to_cache ? (void *)w.kv_cache[l] : (void *)w.qkv;
+        if (fused_rope) {
+            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, wqkv, qkv_out, M, d, c.head_dim, w.rope, r.L, r.pos_d, lq, sc));
+        } else {
+            HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, wqkv, qkv_out, M, 3 * d, d, kGemmMaxSplits, lq, sc));
+            HIP_TRY(h, launch_rope(st, qkv_out, w.rope, r.B, r.L, c.n_heads, c.head_dim, c.rope_theta));
+        }
+        if (r.kv_rows) {
+            if (!r.to_cache) HIP_TRY(h, launch_scatter_kv(st, w.qkv, w.kv_cache[l], r.rows_d, M, d));
+            HIP_TRY(h, launch_attention_rows(st, qkv_out, w.kv_cache[l], w.att, r.B, r.L, c.n_heads, c.head_dim, *r.kv_rows, pd));
+        } else {
+            HIP_TRY(h, launch_attention(st, w.qkv, w.att, r.B, r.L, c.n_heads, c.head_dim, pd));
+        }
+        if (int rc = residual_product(w.att, pd ? h->wo_p[l] : h->wo[l], d, GemmLayout{pd, pd ? d : 0, 0}, h->ffn_norm[l])) return rc;
+        const bool prof = h->prof_on && h->prof_used < h->prof_cap;
+        if (prof) HIP_TRY(h, hipEventRecord(h->prof_ev[2 * h->prof_used], st));
+        HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, pd ? h->w_gate_up_p[l] : h->w_gate_up[l], w.act, M, 2 * f, d,
+                               kGemmMaxSplits, GemmLayout{pd, pd ? 2 * f : 0, pf}, sc));
+        if (prof) HIP_TRY(h, hipEventRecord(h->prof_ev[2 * h->prof_used++ + 1], st));
+        if (int rc = residual_product(w.act, pf ? h->w_down_p[l] : h->w_down[l], f, GemmLayout{pf, pf ? d : 0, 0},
+                                      l + 1 < c.n_layers ? h->attn_norm[l + 1] : h->final_norm)) return rc;
+    }
+    *scale = sc;
+    return DLLM_OK;
+}
+
 // `win` (nullable): per-sequence windows; the vocabulary projection then only
 // covers the rows lo..hi of each sequence (the rows the selector reads).
 // `mask` (nullable): see vocab_rows.
 int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const SelectArgs *win, const uint8_t *mask = nullptr)
 {
-    const dllm_config &c = h->cfg;
-    const int M = B * L, d = c.d_model, f = c.d_ffn;
-    Workspace &w = h->ws;
-    hipStream_t st = h->stream;
-    HIP_TRY(h, launch_embed(st, tokens, nullptr, h->embed, w.x, M, d, c.vocab, w.bad_token));
-    const int slabs = slab_limit(h, M);
-    if (slabs < 1) return fail(h, DLLM_ESTATE, "the split-K workspace does not hold one slab of %d rows", M);
-    const PanelChoice pc = pick_panels(h, M);
-    const int pd = pc.d_rows, pf = pc.f_rows;
-    int pending = 0;  // fp32 slabs waiting to be added to the residual stream
-    for (int l = 0; l < c.n_layers; ++l) {
-        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->attn_norm[l], w.h, M, d, c.rms_eps, pd));
-        const void *wqkv = pd ? h->wqkv_p[l] : h->wqkv[l];
-        if (gemm_qkv_rope_supported(M, d, c.head_dim)) {
-            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, wqkv, w.qkv, M, d, c.head_dim, w.rope, L, nullptr,
-                                            GemmLayout{pd, pd ? 3 * d : 0, 0}));
-        } else {
-            HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, wqkv, w.qkv, M, 3 * d, d, kGemmMaxSplits, GemmLayout{pd, pd ? 3 * d : 0, 0}));
-            HIP_TRY(h, launch_rope(st, w.qkv, w.rope, B, L, c.n_heads, c.head_dim, c.rope_theta));
-        }
-        HIP_TRY(h, launch_attention(st, w.qkv, w.att, B, L, c.n_heads, c.head_dim, pd));
-        pending = gemm_num_splits(M, d, d, slabs);
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, pd ? h->wo_p[l] : h->wo[l], w.partials, M, d, d, slabs,
-                               GemmLayout{pd, pd ? d : 0, 0}));
-        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->ffn_norm[l], w.h, M, d, c.rms_eps, pd));
-        const bool prof = h->prof_on && h->prof_used < h->prof_cap;
-        if (prof) HIP_TRY(h, hipEventRecord(h->prof_ev[2 * h->prof_used], st));
-        HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, pd ? h->w_gate_up_p[l] : h->w_gate_up[l], w.act, M, 2 * f, d,
-                               kGemmMaxSplits, GemmLayout{pd, pd ? 2 * f : 0, pf}));
-        if (prof) HIP_TRY(h, hipEventRecord(h->prof_ev[2 * h->prof_used++ + 1], st));
-        pending = gemm_num_splits(M, d, f, slabs);
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, pf ? h->w_down_p[l] : h->w_down[l], w.partials, M, d, f, slabs,
-                               GemmLayout{pf, pf ? d : 0, 0}));
-    }
-    HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, M, d, c.rms_eps, pd));
+    const int M = B * L;
+    LayerRun r;
+    r.rows = M; r.B = B; r.L = L;
+    int pd = 0;
+    RowScale sc;
+    if (int rc = run_layers(h, tokens, r, &pd, &sc)) return rc;
     if (!win) {
-        if (int rc = vocab_rows(h, 0, 0, M, L, nullptr, nullptr, pd)) return rc;
+        if (int rc = vocab_rows(h, 0, 0, M, L, nullptr, nullptr, pd, sc)) return rc;
     } else {
         // merge sequences whose windows make one contiguous run of rows (always true for B = 1)
         int b = 0;
@@ -277,7 +344,7 @@ int forward_impl(dllm_handle *h, int B, int L, const int32_t *tokens, const Sele
                 last = (long)e * L + win->w[e].hi;
                 ++e;
             }
-            if (int rc = vocab_rows(h, first, first, (int)(last - first + 1), L, mask, win, pd)) return rc;
+            if (int rc = vocab_rows(h, first, first, (int)(last - first + 1), L, mask, win, pd, sc)) return rc;
             b = e;
         }
     }
@@ -294,7 +361,7 @@ int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, con
                         const uint8_t *mask)
 {
     const dllm_config &c = h->cfg;
-    const int d = c.d_model, f = c.d_ffn;
+    const int d = c.d_model;
     Workspace &w = h->ws;
     hipStream_t st = h->stream;
     if (!gemm_qkv_rope_supported(B * L, d, c.head_dim))
@@ -335,36 +402,12 @@ int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, con
     HIP_TRY(h, hipMemcpyAsync(w.pos_d, pos, (size_t)Ma * sizeof(int32_t), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipEventRecord(w.rows_copied[slot], st));
 
-    HIP_TRY(h, launch_embed(st, tokens, w.rows_d, h->embed, w.x, Ma, d, c.vocab, w.bad_token));
-    const int slabs = slab_limit(h, Ma);
-    if (slabs < 1) return fail(h, DLLM_ESTATE, "the split-K workspace does not hold one slab of %d rows", Ma);
-    const PanelChoice pc = pick_panels(h, Ma);
-    const int pd = pc.d_rows, pf = pc.f_rows;
-    int pending = 0;
-    for (int l = 0; l < c.n_layers; ++l) {
-        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->attn_norm[l], w.h, Ma, d, c.rms_eps, pd));
-        const void *wqkv = pd ? h->wqkv_p[l] : h->wqkv[l];
-        const GemmLayout lq{pd, pd ? 3 * d : 0, 0};
-        if (!any_skip) {
-            // everything is recomputed: the projection writes straight into the layer's cache
-            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, wqkv, w.kv_cache[l], Ma, d, c.head_dim, w.rope, L, w.pos_d, lq));
-            HIP_TRY(h, launch_attention_rows(st, w.kv_cache[l], w.kv_cache[l], w.att, B, L, c.n_heads, c.head_dim, sr, pd));
-        } else {
-            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, wqkv, w.qkv, Ma, d, c.head_dim, w.rope, L, w.pos_d, lq));
-            HIP_TRY(h, launch_scatter_kv(st, w.qkv, w.kv_cache[l], w.rows_d, Ma, d));
-            HIP_TRY(h, launch_attention_rows(st, w.qkv, w.kv_cache[l], w.att, B, L, c.n_heads, c.head_dim, sr, pd));
-        }
-        pending = gemm_num_splits(Ma, d, d, slabs);
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.att, pd ? h->wo_p[l] : h->wo[l], w.partials, Ma, d, d, slabs,
-                               GemmLayout{pd, pd ? d : 0, 0}));
-        HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->ffn_norm[l], w.h, Ma, d, c.rms_eps, pd));
-        HIP_TRY(h, launch_gemm(st, kEpiSwiglu, w.h, pd ? h->w_gate_up_p[l] : h->w_gate_up[l], w.act, Ma, 2 * f, d,
-                               kGemmMaxSplits, GemmLayout{pd, pd ? 2 * f : 0, pf}));
-        pending = gemm_num_splits(Ma, d, f, slabs);
-        HIP_TRY(h, launch_gemm(st, kEpiPartial, w.act, pf ? h->w_down_p[l] : h->w_down[l], w.partials, Ma, d, f, slabs,
-                               GemmLayout{pf, pf ? d : 0, 0}));
-    }
-    HIP_TRY(h, launch_add_rmsnorm(st, w.x, w.partials, pending, h->final_norm, w.h, Ma, d, c.rms_eps, pd));
+    LayerRun r;
+    r.rows = Ma; r.B = B; r.L = L; r.rows_d = w.rows_d; r.pos_d = w.pos_d; r.kv_rows = &sr;
+    r.to_cache = !any_skip;   // everything is recomputed: the QKV projection writes straight into the layer's cache
+    int pd = 0;
+    RowScale sc;
+    if (int rc = run_layers(h, tokens, r, &pd, &sc)) return rc;
     // logits stay indexed by absolute row; the rows of a window are consecutive among the recomputed ones
     for (int b = 0; b < B; ++b) {
         const SeqWindow &sw = win.w[b];
@@ -374,7 +417,7 @@ int forward_cached_impl(dllm_handle *h, int B, int L, const int32_t *tokens, con
         for (int i = 0; i < sw.lo; ++i) first_cmp += !(skip && skip[(size_t)b * L + i]);
         for (int i = sw.lo; i <= sw.eval_hi; ++i)
             if (skip && skip[(size_t)b * L + i]) return fail(h, DLLM_EINVAL, "sequence %d: position %d is skipped but inside the window", b, i);
-        if (int rc = vocab_rows(h, first_cmp, first_abs, (int)n, L, mask, &win, pd)) return rc;
+        if (int rc = vocab_rows(h, first_cmp, first_abs, (int)n, L, mask, &win, pd, sc)) return rc;
     }
     if (!any_skip) { w.cache_valid = true; w.cache_B = B; w.cache_L = L; }
     h->last_B = B;
@@ -583,6 +626,12 @@ int dllm_create(const dllm_config *cfg, const dllm_weights *w, void *hip_stream,
     if (2 * M > slab_rows) slab_rows = 2 * M;
     s.partials_cap = slab_rows * d;
     A(dev_alloc(h, &s.partials, s.partials_cap));
+    s.ssq_stride = gemm_residual_max_parts((int)d);
+    A(dev_alloc(h, &s.ssq, M * (size_t)s.ssq_stride));
+    s.n_tickets = (int)(((M + 63) / 64) * ((d + 63) / 64));
+    A(dev_alloc(h, &s.tickets, (size_t)s.n_tickets));
+    if (rc == DLLM_OK && hipMemsetAsync(s.tickets, 0, (size_t)s.n_tickets * sizeof(int32_t), h->stream) != hipSuccess)
+        rc = fail(h, DLLM_EHIP, "dllm_create: hipMemsetAsync failed");
     A(dev_alloc(h, &s.rowstats, 3 * gemm_rowstats_max_parts(c.vocab) * M));
     A(dev_alloc(h, &s.pred, M));
     A(dev_alloc(h, &s.conf, M));
@@ -615,6 +664,8 @@ int dllm_create(const dllm_config *cfg, const dllm_weights *w, void *hip_stream,
         rc = fail(h, DLLM_EHIP, "dllm_create: hipEventCreate failed");
     if (rc == DLLM_OK && launch_rope_table(h->stream, s.rope, c.max_seq, c.head_dim, c.rope_theta) != hipSuccess)
         rc = fail(h, DLLM_EHIP, "dllm_create: rope table launch failed");
+    h->fused_norm = getenv("DLLM_NO_FUSED_NORM") == nullptr;
+    h->fused_splitk = getenv("DLLM_FUSED_SPLITK") != nullptr;
     // panel-major copies of the weights (the caller's stay in use for shapes the asynchronous-copy kernel does not take)
     if (rc == DLLM_OK && getenv("DLLM_NO_PACK") == nullptr) {
         auto pack = [&](const void *src, size_t rows, size_t K, const void **dst) {

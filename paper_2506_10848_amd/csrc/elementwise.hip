@@ -11,24 +11,52 @@ constexpr int kThreads = 256;
 
 // x[r][:] = float(E[tokens[r]][:]); d % 8 == 0.  An id outside [0, vocab) is never used as an index:
 // its row becomes zeros and *bad_token is set to 1 (the host reports it at its next synchronisation).
+// With gain != null the kernel also leaves what the first projection needs to apply the first RMSNorm
+// itself: h[r][:] = bf16(x[r][:] * gain[:]) (row-major, or panel-major with h_panel_rows rows per panel)
+// and ssq[r * ssq_stride] = sum of x[r][:]^2.
 __global__ __launch_bounds__(kThreads) void embed_kernel(const int32_t *__restrict__ tokens,
                                                          const int32_t *__restrict__ rows,
                                                          const uint16_t *__restrict__ E, float *__restrict__ x, int d,
-                                                         int vocab, int32_t *__restrict__ bad_token)
+                                                         int vocab, int32_t *__restrict__ bad_token,
+                                                         const uint16_t *__restrict__ gain, uint16_t *__restrict__ h,
+                                                         int h_panel_rows, float *__restrict__ ssq, int ssq_stride)
 {
+    __shared__ float wsum[kThreads / kWave];
     const int r = blockIdx.x;
     const int tok = tokens[rows ? rows[r] : r];
+    const bool bad = (unsigned)tok >= (unsigned)vocab;  // uniform over the workgroup
     float4 *dst = reinterpret_cast<float4 *>(x + (size_t)r * d);
-    if ((unsigned)tok >= (unsigned)vocab) {  // uniform over the workgroup
-        for (int c = threadIdx.x; c < d / 4; c += kThreads) dst[c] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (threadIdx.x == 0 && bad_token) *bad_token = 1;
-        return;
-    }
-    const uint4 *src = reinterpret_cast<const uint4 *>(E + (size_t)tok * d);
+    const uint4 *src = reinterpret_cast<const uint4 *>(E + (size_t)(bad ? 0 : tok) * d);
+    if (bad && threadIdx.x == 0 && bad_token) *bad_token = 1;
+    float ss = 0.0f;
     for (int c = threadIdx.x; c < d / 8; c += kThreads) {
-        const uint4 q = src[c];
-        dst[2 * c] = make_float4(bf16_lo(q.x), bf16_hi(q.x), bf16_lo(q.y), bf16_hi(q.y));
-        dst[2 * c + 1] = make_float4(bf16_lo(q.z), bf16_hi(q.z), bf16_lo(q.w), bf16_hi(q.w));
+        const uint4 q = bad ? make_uint4(0, 0, 0, 0) : src[c];
+        const float4 lo = make_float4(bf16_lo(q.x), bf16_hi(q.x), bf16_lo(q.y), bf16_hi(q.y));
+        const float4 hi = make_float4(bf16_lo(q.z), bf16_hi(q.z), bf16_lo(q.w), bf16_hi(q.w));
+        dst[2 * c] = lo;
+        dst[2 * c + 1] = hi;
+        if (gain) {
+            ss += lo.x * lo.x + lo.y * lo.y + lo.z * lo.z + lo.w * lo.w + hi.x * hi.x + hi.y * hi.y + hi.z * hi.z + hi.w * hi.w;
+            const uint4 g = reinterpret_cast<const uint4 *>(gain)[c];
+            uint4 o;
+            o.x = pack_bf16x2(lo.x * bf16_lo(g.x), lo.y * bf16_hi(g.x));
+            o.y = pack_bf16x2(lo.z * bf16_lo(g.y), lo.w * bf16_hi(g.y));
+            o.z = pack_bf16x2(hi.x * bf16_lo(g.z), hi.y * bf16_hi(g.z));
+            o.w = pack_bf16x2(hi.z * bf16_lo(g.w), hi.w * bf16_hi(g.w));
+            // elements 8c .. 8c+7 of row r: panel c / 4, 16-byte slot c % 4 of the row's 64 bytes
+            if (h_panel_rows) reinterpret_cast<uint4 *>(h)[((size_t)(c >> 2) * h_panel_rows + r) * 4 + (c & 3)] = o;
+            else reinterpret_cast<uint4 *>(h + (size_t)r * d)[c] = o;
+        }
+    }
+    if (!gain) return;
+    ss = wave_sum(ss);
+    if ((threadIdx.x & (kWave - 1)) == 0) wsum[threadIdx.x / kWave] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float tot = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kThreads / kWave; ++w) tot += wsum[w];
+        ssq[(size_t)r * ssq_stride] = tot;
     }
 }
 
@@ -150,10 +178,12 @@ __global__ __launch_bounds__(kThreads) void rope_kernel(uint16_t *__restrict__ q
 }  // namespace
 
 hipError_t launch_embed(hipStream_t stream, const int32_t *tokens, const int32_t *rows, const void *embed, float *x,
-                        int M, int d, int vocab, int32_t *bad_token)
+                        int M, int d, int vocab, int32_t *bad_token, const void *gain, void *h, int h_panel_rows,
+                        float *ssq, int ssq_stride)
 {
+    if (gain && (!h || !ssq || ssq_stride < 1 || (h_panel_rows && (d % 32 || h_panel_rows < M)))) return hipErrorInvalidValue;
     hipLaunchKernelGGL(embed_kernel, dim3(M), dim3(kThreads), 0, stream, tokens, rows, (const uint16_t *)embed, x, d,
-                       vocab, bad_token);
+                       vocab, bad_token, (const uint16_t *)gain, (uint16_t *)h, h_panel_rows, ssq, ssq_stride);
     return hipGetLastError();
 }
 

@@ -143,9 +143,22 @@ struct RopeArgs {
     // 32-element K panels of A and of W, and the panel rows of a panel-major SwiGLU output (0: row-major).
     uint32_t a_row_pitch, a_panel_pitch, w_row_pitch, w_panel_pitch;
     int c_panel_rows;
+    // RMSNorm folded into the product that consumes the normalised rows (see RowScale): every output row r is
+    // scaled by rsqrt(sum_p row_ssq[r * ssq_stride + p] / K + eps) before its epilogue.  Null: no scaling.
+    const float *row_ssq;
+    int ssq_parts, ssq_stride;
+    float eps;
+    // Residual epilogue (see ResidualOut); Cout then holds the fp32 split-K slabs.
+    float *x;
+    const uint16_t *gain;
+    uint16_t *h_out;
+    float *ssq_out;
+    int *tickets;
+    int ssq_out_stride;
 };
 constexpr int kEpiRope64 = 3, kEpiRope128 = 4;  // head_dim is a compile-time constant of the epilogue
 constexpr int kEpiRowStats = 5;
+constexpr int kEpiResidual = 6;  // the O and down projections: see residual_tile
 
 __host__ __device__ constexpr bool epi_paired(int epi) { return epi == kEpiSwiglu || epi == kEpiRope64 || epi == kEpiRope128; }
 __host__ __device__ constexpr int epi_head_dim(int epi) { return epi == kEpiRope128 ? 128 : 64; }
@@ -172,9 +185,12 @@ __device__ __forceinline__ int w_global_row(int j, int n0, int N)
 // column (plain) or the first pair (paired) of the workgroup's tile.
 // GUARD = false: the workgroup's tile lies inside the matrix and N % 4 == 0, so no store needs a
 // bounds check (straight-line stores with immediate offsets instead of a masked branch per store).
+// s_inv (LDS, nullable): per row of the workgroup's tile, the factor every accumulator of that row is
+// multiplied with where the epilogue reads it (the RMSNorm of the rows that were multiplied, see RowScale).
 template <int TM, int TN, int WTM, int EPI, bool GUARD>
 __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, int M, int N, int m0, int n0, int wm,
-                                           int wn, int l32, int lhalf, int split, const RopeArgs &rope)
+                                           int wn, int l32, int lhalf, int split, const RopeArgs &rope,
+                                           const float *s_inv = nullptr)
 {
     if constexpr (EPI == kEpiRowStats) {
         // Cout: fp32 max [parts][M], fp32 sum of exp(x - max) [parts][M], int32 lowest column of the max
@@ -186,6 +202,7 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row = m0 + wm * WTM + i * 32 + l32;
+            const float inv = s_inv ? s_inv[wm * WTM + i * 32 + l32] : 1.0f;
             float m = kNegBig;
             int c = 0x7fffffff;
 #pragma unroll
@@ -193,8 +210,8 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int col = n0 + (wn * TN + j) * 32 + 8 * q + 4 * lhalf;
-                    const uint32_t w01 = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
-                    const uint32_t w23 = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                    const uint32_t w01 = pack_bf16x2(acc[i][j][4 * q] * inv, acc[i][j][4 * q + 1] * inv);
+                    const uint32_t w23 = pack_bf16x2(acc[i][j][4 * q + 2] * inv, acc[i][j][4 * q + 3] * inv);
                     const float x[4] = {__uint_as_float(w01 << 16), __uint_as_float(w01 & 0xffff0000u),
                                         __uint_as_float(w23 << 16), __uint_as_float(w23 & 0xffff0000u)};
 #pragma unroll
@@ -233,6 +250,7 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row = m0 + wm * WTM + i * 32 + l32;
+            const float inv = s_inv ? s_inv[wm * WTM + i * 32 + l32] : 1.0f;
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -241,7 +259,7 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
                     float y[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float g = acc[i][j][4 * q + e], u = acc[i][j][8 + 4 * q + e];
+                        const float g = acc[i][j][4 * q + e] * inv, u = acc[i][j][8 + 4 * q + e] * inv;
                         y[e] = g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;  // 1 ulp reciprocal, far below the bf16 rounding
                     }
                     if (GUARD && (row >= M || col >= n_out)) continue;
@@ -268,6 +286,7 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
         for (int i = 0; i < TM; ++i) {
             const int row = m0 + wm * WTM + i * 32 + l32;
             const float2 *trow = rope.table + (size_t)(rope.pos ? rope.pos[min(row, M - 1)] : row % rope.L) * HD;
+            const float inv = s_inv ? s_inv[wm * WTM + i * 32 + l32] : 1.0f;
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -278,8 +297,8 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
                     float a[4], b[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        a[e] = acc[i][j][4 * q + e];
-                        b[e] = acc[i][j][8 + 4 * q + e];
+                        a[e] = acc[i][j][4 * q + e] * inv;
+                        b[e] = acc[i][j][8 + 4 * q + e] * inv;
                     }
                     if (col < rope.rope_cols) {
                         const float4 *tp = reinterpret_cast<const float4 *>(trow + pp);  // 4 (cos, sin) pairs
@@ -306,6 +325,7 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row = m0 + wm * WTM + i * 32 + l32;
+            const float inv = s_inv ? s_inv[wm * WTM + i * 32 + l32] : 1.0f;
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -315,11 +335,11 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
                     uint16_t *p = C + (size_t)row * N + col;
                     if (!GUARD || (col + 3 < N && (N & 3) == 0)) {
                         uint2 w;
-                        w.x = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
-                        w.y = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                        w.x = pack_bf16x2(acc[i][j][4 * q] * inv, acc[i][j][4 * q + 1] * inv);
+                        w.y = pack_bf16x2(acc[i][j][4 * q + 2] * inv, acc[i][j][4 * q + 3] * inv);
                         *reinterpret_cast<uint2 *>(p) = w;
                     } else {
-                        for (int e = 0; e < 4 && col + e < N; ++e) p[e] = float_to_bf16_bits(acc[i][j][4 * q + e]);
+                        for (int e = 0; e < 4 && col + e < N; ++e) p[e] = float_to_bf16_bits(acc[i][j][4 * q + e] * inv);
                     }
                 }
         }
@@ -343,6 +363,134 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
                     }
                 }
         }
+    }
+}
+
+// Residual epilogue of the O and down projections.  The workgroup that runs it holds the tile's last
+// missing partial product in its accumulators; the other K splits' partial tiles are in the slabs.
+//   x[row][col] += partial_0 + partial_1 + ...        (fp32 residual stream, in split order)
+//   h_out[row][col] = bf16(x[row][col] * gain[col])   (operand of the next projection, not yet normalised:
+//                                                      that product scales its rows, see RowScale)
+//   ssq_out[row][part] = sum over this wave's columns of x[row][col]^2, part = (column tile, wave column)
+// FROM_SLABS = false: one K split, the accumulators are the whole product.  FROM_SLABS = true: every split's
+// partial tile (this workgroup's too) is read back from the slabs and added in split order, so the sum does
+// not depend on which split came last.
+template <int TM, int TN, int WTM, bool FROM_SLABS>
+__device__ __forceinline__ void residual_tile(floatx16 (&acc)[TM][TN], const float *slabs, int splits, int M, int N, int m0,
+                                              int n0, int wm, int wn, int l32, int lhalf, int part, const RopeArgs &ea)
+{
+    const size_t slab = (size_t)M * N;
+    constexpr int NV = TN * 4;        // float4 positions of a lane in one 32-row block
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row = m0 + wm * WTM + i * 32 + l32;
+        float4 v[NV];
+        bool ok[NV];
+#pragma unroll
+        for (int jq = 0; jq < NV; ++jq) {
+            const int col = n0 + (wn * TN + jq / 4) * 32 + 8 * (jq % 4) + 4 * lhalf;
+            ok[jq] = row < M && col < N;                          // (N % 4 == 0: checked by the host)
+            v[jq] = ok[jq] ? *reinterpret_cast<const float4 *>(ea.x + (size_t)row * N + col) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        }
+        if constexpr (FROM_SLABS) {
+            for (int s = 0; s < splits; ++s) {
+                float4 p[NV];
+#pragma unroll
+                for (int jq = 0; jq < NV; ++jq) {
+                    const int col = n0 + (wn * TN + jq / 4) * 32 + 8 * (jq % 4) + 4 * lhalf;
+                    p[jq] = ok[jq] ? *reinterpret_cast<const float4 *>(slabs + s * slab + (size_t)row * N + col)
+                                   : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                }
+#pragma unroll
+                for (int jq = 0; jq < NV; ++jq) { v[jq].x += p[jq].x; v[jq].y += p[jq].y; v[jq].z += p[jq].z; v[jq].w += p[jq].w; }
+            }
+        } else {
+#pragma unroll
+            for (int jq = 0; jq < NV; ++jq) {
+                const int j = jq / 4, q = jq % 4;
+                v[jq].x += acc[i][j][4 * q]; v[jq].y += acc[i][j][4 * q + 1]; v[jq].z += acc[i][j][4 * q + 2]; v[jq].w += acc[i][j][4 * q + 3];
+            }
+        }
+        float ss = 0.0f;
+#pragma unroll
+        for (int jq = 0; jq < NV; ++jq) {
+            if (!ok[jq]) continue;
+            const int col = n0 + (wn * TN + jq / 4) * 32 + 8 * (jq % 4) + 4 * lhalf;
+            const size_t at = (size_t)row * N + col;
+            const float4 t = v[jq];
+            *reinterpret_cast<float4 *>(ea.x + at) = t;
+            ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+            const uint2 g = *reinterpret_cast<const uint2 *>(ea.gain + col);
+            uint2 o;
+            o.x = pack_bf16x2(t.x * bf16_lo(g.x), t.y * bf16_hi(g.x));
+            o.y = pack_bf16x2(t.z * bf16_lo(g.y), t.w * bf16_hi(g.y));
+            uint16_t *hp = ea.c_panel_rows ? ea.h_out + ((size_t)(col >> 5) * ea.c_panel_rows + row) * 32 + (col & 31)
+                                           : ea.h_out + at;
+            *reinterpret_cast<uint2 *>(hp) = o;
+        }
+        ss += __shfl_xor(ss, 32, 64);                               // the other half of the row's columns
+        if (lhalf == 0 && row < M) ea.ssq_out[(size_t)row * ea.ssq_out_stride + part] = ss;
+    }
+}
+
+// The tail of a kEpiResidual workgroup: with one K split the accumulators are the whole product; with more,
+// every split leaves its partial tile in its slab and takes a ticket, and the split that takes the last ticket
+// of a tile adds everything up (the others are done).  No workgroup waits for another.
+template <int TM, int TN, int WTM, int WN>
+__device__ __forceinline__ void residual_finish(floatx16 (&acc)[TM][TN], void *slabs, int M, int N, int m0, int n0, int wm,
+                                                int wn, int l32, int lhalf, int pid_n, const RopeArgs &ea)
+{
+    __shared__ int s_ticket;
+    const int splits = gridDim.y, my_split = blockIdx.y;
+    if (splits > 1) {
+        store_tile<TM, TN, WTM, kEpiPartial, true>(acc, slabs, M, N, m0, n0, wm, wn, l32, lhalf, my_split, ea);
+        // One thread publishes for the workgroup: the barrier orders every thread's slab stores before its
+        // device-scope release (a single write-back of the L2 per workgroup instead of one per wave), the
+        // ticket is taken, and only the workgroup that finds itself last pays for the acquire (which drops
+        // what its L2 holds of other workgroups' lines).  The second barrier hands the result to the others.
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            const int t = __hip_atomic_fetch_add(&ea.tickets[blockIdx.x], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (t == splits - 1) {
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                ea.tickets[blockIdx.x] = 0;    // ready for the next launch; nobody else looks at it any more
+            }
+            s_ticket = t;
+        }
+        __syncthreads();
+        if (s_ticket != splits - 1) return;    // uniform over the workgroup
+    }
+    if (splits > 1)
+        residual_tile<TM, TN, WTM, true>(acc, reinterpret_cast<const float *>(slabs), splits, M, N, m0, n0, wm, wn, l32, lhalf,
+                                         pid_n * WN + wn, ea);
+    else
+        residual_tile<TM, TN, WTM, false>(acc, nullptr, 1, M, N, m0, n0, wm, wn, l32, lhalf, pid_n * WN + wn, ea);
+}
+
+// RowScale: the factors of the workgroup's BM rows, rsqrt(mean square + eps) from the partial sums of squares
+// that the producer of the rows left (embedding kernel or a residual epilogue), summed in part order.
+template <int BM>
+__device__ __forceinline__ void row_scale_prologue(float *s_inv, int m0, int M, int K, const RopeArgs &ea)
+{
+    if (!ea.row_ssq) return;
+    for (int t = threadIdx.x; t < BM; t += blockDim.x) {
+        const float *p = ea.row_ssq + (size_t)min(m0 + t, M - 1) * ea.ssq_stride;
+        float sum = 0.0f;
+        if (((ea.ssq_parts | ea.ssq_stride) & 3) == 0) {   // rows of whole, aligned float4
+            const float4 *p4 = reinterpret_cast<const float4 *>(p);
+            const int n4 = ea.ssq_parts >> 2;
+            for (int k0 = 0; k0 < n4; k0 += 8) {           // eight loads in flight, summed in part order
+                float4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = k0 + u < n4 ? p4[k0 + u] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) sum += (v[u].x + v[u].y) + (v[u].z + v[u].w);
+            }
+        } else {
+            for (int k = 0; k < ea.ssq_parts; ++k) sum += p[k];
+        }
+        s_inv[t] = rsqrtf(sum / (float)K + ea.eps);
     }
 }
 
@@ -438,7 +586,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
 
     // every kernel argument the epilogue needs is in registers before the loop (see the file header)
     asm volatile("" ::"s"(Cout), "s"(M), "s"(N), "s"(rope.table), "s"(rope.pos), "s"(rope.L), "s"(rope.rope_cols),
-                 "s"(rope.c_panel_rows));
+                 "s"(rope.c_panel_rows), "s"(rope.row_ssq), "s"(rope.x), "s"(rope.gain), "s"(rope.h_out), "s"(rope.ssq_out),
+                 "s"(rope.tickets), "s"(rope.ssq_out_stride));
+    __shared__ float s_inv[BM];
+    row_scale_prologue<BM>(s_inv, m0, M, K, rope);   // (its loads are complete before the first copy is issued)
 
 #pragma unroll
     for (int s = 0; s < P; ++s)
@@ -514,14 +665,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_il_kernel(const uint16_t *_
     else k_loop(std::false_type{});
 #undef DLLM_COPY
 #undef DLLM_READ
+    if constexpr (EPI == kEpiResidual) {
+        residual_finish<TM, TN, WTM, WN>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, pid_n, rope);
+        return;
+    }
+    const float *inv = rope.row_ssq ? s_inv : nullptr;   // written before the K loop's barriers
     const int n_lim = epi_paired(EPI) ? N / 2 : N;
     if constexpr (kSkipEmpty) {  // (the 256x256 tile has no register to spare for a second epilogue)
         if (m0 + BM <= M && n0 + BN_OUT <= n_lim && (n_lim & 3) == 0 && (N & 3) == 0) {
-            store_tile<TM, TN, WTM, EPI, false>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
+            store_tile<TM, TN, WTM, EPI, false>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope, inv);
             return;
         }
     }
-    store_tile<TM, TN, WTM, EPI, true>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
+    store_tile<TM, TN, WTM, EPI, true>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope, inv);
 }
 
 // ---- fallback kernel: any K % 8 == 0 -------------------------------------------
@@ -586,6 +742,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *
 #pragma unroll
     for (int j = 0; j < TN; ++j) b_row[j] = (BM + wn * WTN + j * 32 + l32) * kChunksPerRow;
     const int sw = (l32 >> 1) & 7;
+    __shared__ float s_inv[BM];
+    row_scale_prologue<BM>(s_inv, m0, M, K, rope);   // (read after the loop's barriers)
 
     for (int kt = 0; kt <= nk; ++kt) {
         // registers of step kt-1 go to LDS, step kt is fetched, step kt-1 is multiplied
@@ -622,7 +780,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_reg_kernel(const uint16_t *
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
     }
-    store_tile<TM, TN, WTM, EPI, true>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope);
+    if constexpr (EPI == kEpiResidual) {
+        residual_finish<TM, TN, WTM, WN>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, pid_n, rope);
+        return;
+    }
+    store_tile<TM, TN, WTM, EPI, true>(acc, Cout, M, N, m0, n0, wm, wn, l32, lhalf, blockIdx.y, rope,
+                                       rope.row_ssq ? s_inv : nullptr);
 }
 
 // ---- host side ----------------------------------------------------------------
@@ -661,10 +824,10 @@ struct Plan {
 // Test and tuning hooks from the environment, read once (and again by gemm_reload_env): DLLM_GEMM_FALLBACK
 // forces the register-staged kernel, DLLM_NO_FUSED_ROPE the separate rotary kernel, DLLM_GEMM_CFG a tile
 // shape for every product, DLLM_GEMM_CFG_E<epilogue> for one epilogue, DLLM_GEMM_SPLITS a split count.
-constexpr int kNumEpi = 6;
+constexpr int kNumEpi = 7;
 struct EnvHooks {
     bool loaded = false;
-    int fallback = 0, no_fused_rope = 0, cfg_all = -1, cfg_epi[kNumEpi] = {-1, -1, -1, -1, -1, -1}, splits = -1;
+    int fallback = 0, no_fused_rope = 0, cfg_all = -1, cfg_epi[kNumEpi] = {-1, -1, -1, -1, -1, -1, -1}, splits = -1;
 };
 std::mutex g_plan_mutex;  // guards g_env and g_plans
 EnvHooks g_env;
@@ -703,7 +866,7 @@ bool cfg_allows(int c, int epi, bool fast)
     if (!fast && c < 2) return false;  // the register-staged kernel keeps to the smaller tiles
     // 256 accumulator registers per lane leave no room for the addresses of the fp32 epilogue (and at
     // N = 4096 it measured no faster than the 256x128 tile)
-    if (c == 0 && epi == kEpiPartial) return false;
+    if (c == 0 && (epi == kEpiPartial || epi == kEpiResidual)) return false;
     // a wave's slice of a row is at least 64 columns wide, which bounds the partial results per row
     if (epi == kEpiRowStats && kCfg[c].bn / kCfg[c].wn < 64) return false;
     return true;
@@ -719,7 +882,8 @@ Plan search_plan(const EnvHooks &env, int epi, int M, int N, int K, int split_li
     const int fc = (epi >= 0 && epi < kNumEpi && env.cfg_epi[epi] >= 0) ? env.cfg_epi[epi] : env.cfg_all, fs = env.splits;
     Plan best{4, 1, fast};
     double best_cost = 1e300;
-    const int max_splits = epi == kEpiPartial ? (split_limit < 1 ? 1 : split_limit > kGemmMaxSplits ? kGemmMaxSplits : split_limit) : 1;
+    const bool splittable = epi == kEpiPartial || epi == kEpiResidual;
+    const int max_splits = splittable ? (split_limit < 1 ? 1 : split_limit > kGemmMaxSplits ? kGemmMaxSplits : split_limit) : 1;
     for (int c = 0; c < kNumCfg; ++c) {
         if (!cfg_allows(c, epi, fast) || (fc >= 0 && fc < kNumCfg && cfg_allows(fc, epi, fast) && c != fc)) continue;
         // a single row of 256x256 tiles that only streams W (the vocabulary projection of one window) measures
@@ -747,7 +911,7 @@ Plan search_plan(const EnvHooks &env, int epi, int M, int N, int K, int split_li
             const long cap = (long)kNumCU * per_cu;  // a partly filled last round streams at a lower rate
             const double stream = (double)N * K * 2.0 / bw * (wgs > cap ? (double)((wgs + cap - 1) / cap * cap) / (double)wgs : 1.0);
             double cost = (compute > stream ? compute : stream) + (double)rounds * (t.epi_us + 1.5);
-            if (epi == kEpiPartial) cost += (double)s * M * N * 8.0 / 4.0e6;  // slab write + read, ~4 TB/s
+            if (splittable) cost += (double)s * M * N * 8.0 / 4.0e6;  // slab write + read, ~4 TB/s
             if (cost < best_cost) { best_cost = cost; best = Plan{c, s, fast}; }
         }
     }
@@ -769,9 +933,14 @@ Plan make_plan(int epi, int M, int N, int K, int split_limit = kGemmMaxSplits)
 
 // Pitches of the kernel's operand addressing for a layout (see the kernel); false if a panel-major operand
 // is asked of a kernel that cannot read it or does not fit 32-bit offsets.
+void set_scale(RopeArgs &r, const RowScale &sc)
+{
+    r.row_ssq = sc.ssq; r.ssq_parts = sc.parts; r.ssq_stride = sc.stride; r.eps = sc.eps;
+}
+
 bool set_layout(RopeArgs &r, const GemmLayout &lay, bool fast, int K)
 {
-    if (!fast && (lay.a_panel_rows || lay.w_panel_rows || lay.c_panel_rows)) return false;
+    if (!fast && (lay.a_panel_rows || lay.w_panel_rows)) return false;   // (outputs are written by the shared epilogues)
     if ((double)lay.a_panel_rows * 64 * 2 >= 4.0e9 || (double)lay.w_panel_rows * 64 * 2 >= 4.0e9) return false;
     r.a_row_pitch = lay.a_panel_rows ? 64u : (uint32_t)K * 2u;
     r.a_panel_pitch = lay.a_panel_rows ? (uint32_t)lay.a_panel_rows * 64u : 64u;
@@ -815,12 +984,12 @@ hipError_t launch_cfg(hipStream_t stream, bool fast, const void *A, const void *
 
 template <int EPI>
 hipError_t dispatch(hipStream_t stream, Plan p, const void *A, const void *W, void *C, int M, int N, int K,
-                    const GemmLayout &lay, RopeArgs rope = RopeArgs{nullptr, nullptr, {1}, {0}, 0, 0, 0, 0, 0})
+                    const GemmLayout &lay, RopeArgs rope = RopeArgs{})
 {
     if (!set_layout(rope, lay, p.fast, K)) return hipErrorInvalidValue;
     switch (p.cfg) {
     case 0:
-        if constexpr (EPI != kEpiPartial)
+        if constexpr (EPI != kEpiPartial && EPI != kEpiResidual)
             return launch_cfg<256, 256, 2, 2, 32, 4, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
         return hipErrorInvalidValue;  // never planned: see cfg_allows
     case 1: return launch_cfg<256, 192, 2, 2, 32, 5, EPI>(stream, p.fast, A, W, C, M, N, K, p.splits, rope);
@@ -862,9 +1031,11 @@ bool gemm_qkv_rope_supported(int M, int d, int dh)
 }
 
 hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
-                                const float2 *table, int L, const int32_t *pos, const GemmLayout &lay)
+                                const float2 *table, int L, const int32_t *pos, const GemmLayout &lay, const RowScale &scale)
 {
-    const RopeArgs rope{table, pos, {L}, {2 * d}, 0, 0, 0, 0, 0};
+    RopeArgs rope{};
+    rope.table = table; rope.pos = pos; rope.L = L; rope.rope_cols = 2 * d;
+    set_scale(rope, scale);
     const Plan p = make_plan(dh == 128 ? kEpiRope128 : kEpiRope64, M, 3 * d, d);
     if (dh == 128) return dispatch<kEpiRope128>(stream, p, A, W, C, M, 3 * d, d, lay, rope);
     return dispatch<kEpiRope64>(stream, p, A, W, C, M, 3 * d, d, lay, rope);
@@ -873,28 +1044,53 @@ hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W
 size_t gemm_rowstats_max_parts(int N) { return (size_t)(N + 63) / 64 + 1; }
 
 hipError_t launch_gemm_rowstats(hipStream_t stream, const void *A, const void *W, float *stats, int M, int N, int K,
-                                int mask_id, int *parts, const GemmLayout &lay)
+                                int mask_id, int *parts, const GemmLayout &lay, const RowScale &scale)
 {
     const Plan p = make_plan(kEpiRowStats, M, N, K);
     const TileCfg &t = kCfg[p.cfg];
     *parts = (N + t.bn - 1) / t.bn * t.wn;
     if ((size_t)*parts > gemm_rowstats_max_parts(N)) return hipErrorInvalidValue;
-    RopeArgs ea{nullptr, nullptr, {0}, {0}, 0, 0, 0, 0, 0};
+    RopeArgs ea{};
     ea.parts = *parts;
     ea.mask_id = mask_id;
+    set_scale(ea, scale);
     return dispatch<kEpiRowStats>(stream, p, A, W, stats, M, N, K, lay, ea);
 }
 
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
-                       int K, int split_limit, const GemmLayout &lay)
+                       int K, int split_limit, const GemmLayout &lay, const RowScale &scale)
 {
     const Plan p = make_plan(epi, M, N, K, split_limit);
+    RopeArgs ea{};
+    ea.L = 1;
     switch (epi) {
-    case kEpiBf16: return dispatch<kEpiBf16>(stream, p, A, W, C, M, N, K, lay);
-    case kEpiSwiglu: return dispatch<kEpiSwiglu>(stream, p, A, W, C, M, N, K, lay);
-    default: return dispatch<kEpiPartial>(stream, p, A, W, C, M, N, K, lay);
+    case kEpiBf16: set_scale(ea, scale); return dispatch<kEpiBf16>(stream, p, A, W, C, M, N, K, lay, ea);
+    case kEpiSwiglu: set_scale(ea, scale); return dispatch<kEpiSwiglu>(stream, p, A, W, C, M, N, K, lay, ea);
+    default:
+        if (scale.ssq) return hipErrorInvalidValue;   // slabs of partial products cannot be scaled row by row
+        return dispatch<kEpiPartial>(stream, p, A, W, C, M, N, K, lay, ea);
     }
 }
+
+hipError_t launch_gemm_residual(hipStream_t stream, const void *A, const void *W, const ResidualOut &out, int M, int N,
+                                int K, int split_limit, const GemmLayout &lay, int *ssq_parts)
+{
+    if (!out.x || !out.gain || !out.h || !out.ssq || !out.slabs || !out.tickets || (N & 3)) return hipErrorInvalidValue;
+    const Plan p = make_plan(kEpiResidual, M, N, K, split_limit);
+    const TileCfg &t = kCfg[p.cfg];
+    const int num_m = (M + t.bm - 1) / t.bm, num_n = (N + t.bn - 1) / t.bn;
+    *ssq_parts = num_n * t.wn;
+    if (*ssq_parts > out.ssq_stride || (long)num_m * num_n > out.n_tickets) return hipErrorInvalidValue;
+    RopeArgs ea{};
+    ea.L = 1;
+    ea.x = out.x; ea.gain = (const uint16_t *)out.gain; ea.h_out = (uint16_t *)out.h; ea.ssq_out = out.ssq;
+    ea.tickets = out.tickets; ea.ssq_out_stride = out.ssq_stride;
+    GemmLayout l2 = lay;
+    l2.c_panel_rows = out.h_panel_rows;
+    return dispatch<kEpiResidual>(stream, p, A, W, out.slabs, M, N, K, l2, ea);
+}
+
+int gemm_residual_max_parts(int N) { return (N + 63) / 64 * 2; }   // narrowest tile: 64 columns, two wave columns
 
 bool gemm_async_copy_path(int epi, int M, int N, int K, int split_limit)
 {

@@ -39,8 +39,11 @@ hipError_t launch_rowstats_merge(hipStream_t stream, const float *stats, int par
 // ---- forward pass -------------------------------------------------------------
 // rows (nullable): x[r] is the embedding of tokens[rows[r]] instead of tokens[r].  A token id outside
 // [0, vocab) gives a row of zeros and sets *bad_token (device int32, nullable) to 1.
+// gain (nullable): the kernel also leaves the operand of the first projection, h = bf16(x * gain) (row-major,
+// or panel-major with h_panel_rows rows per panel), and ssq[r * ssq_stride] = sum of x[r]^2 (see RowScale).
 hipError_t launch_embed(hipStream_t stream, const int32_t *tokens, const int32_t *rows, const void *embed, float *x,
-                        int M, int d, int vocab, int32_t *bad_token);
+                        int M, int d, int vocab, int32_t *bad_token, const void *gain = nullptr, void *h = nullptr,
+                        int h_panel_rows = 0, float *ssq = nullptr, int ssq_stride = 0);
 // dst[rows[r]][d .. 3d) = src[r][d .. 3d): the k and v thirds of recomputed rows go to their cache rows
 hipError_t launch_scatter_kv(hipStream_t stream, const void *src, void *dst, const int32_t *rows, int n_rows, int d);
 // h_panel_rows != 0: h is written panel-major (see GemmLayout) with that many rows per panel (>= M; d % 32 == 0)
@@ -78,6 +81,34 @@ struct GemmLayout {
     int w_panel_rows = 0;  // 0: W row-major [N][K]; else rows per panel of a panel-major W (all N rows)
     int c_panel_rows = 0;  // kEpiSwiglu only: 0: output row-major [M][N/2]; else rows per panel of the output
 };
+// RMSNorm folded into the product that consumes the normalised rows.  The producer of the rows (the embedding
+// kernel or the residual epilogue of the O / down projection) leaves bf16(x * gain) as the operand and, per
+// row, `parts` partial sums of x^2 (ssq[row * stride + p]); the product then multiplies every output row by
+// rsqrt(sum_p ssq / K + eps) in fp32 before its own epilogue, which is the same map as normalising first.
+struct RowScale {
+    const float *ssq = nullptr;  // null: rows are not scaled
+    int parts = 0, stride = 0;
+    float eps = 0.0f;
+};
+// What the residual product (launch_gemm_residual) updates and leaves for the next product:
+//   x [M][N] fp32 += A W^T;  h = bf16(x * gain) row-major [M][N] or panel-major (h_panel_rows rows per panel);
+//   ssq [M][ssq_stride]: per row, *ssq_parts partial sums of x^2.
+// slabs: workspace for the fp32 partial tiles of split_limit K splits ([split_limit][M][N]); tickets: n_tickets
+// zeroed int32 counters, one per output tile, left zeroed again (>= tiles of the narrowest plan).
+struct ResidualOut {
+    float *x = nullptr;
+    const void *gain = nullptr;
+    void *h = nullptr;
+    int h_panel_rows = 0;
+    float *ssq = nullptr;
+    int ssq_stride = 0;
+    float *slabs = nullptr;
+    int *tickets = nullptr;
+    int n_tickets = 0;
+};
+hipError_t launch_gemm_residual(hipStream_t stream, const void *A, const void *W, const ResidualOut &out, int M, int N,
+                                int K, int split_limit, const GemmLayout &lay, int *ssq_parts);
+int gemm_residual_max_parts(int N);
 // Whether the product will run on the asynchronous-copy kernel (the one that takes panel-major operands).
 bool gemm_async_copy_path(int epi, int M, int N, int K, int split_limit = 8);
 // dst[K / 32][rows][32] (panel-major) = src[rows][K]; K % 32 == 0.
@@ -103,16 +134,18 @@ bool gemm_qkv_rope_supported(int M, int d, int dh);
 // pos (nullable): position of every row; default row % L.
 hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
                                 const float2 *table, int L, const int32_t *pos = nullptr,
-                                const GemmLayout &lay = GemmLayout());
+                                const GemmLayout &lay = GemmLayout(), const RowScale &scale = RowScale());
 // C = A[M][K] * W[N][K]^T.  For kEpiSwiglu N counts gate + up rows.
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
-                       int K, int split_limit = kGemmMaxSplits, const GemmLayout &lay = GemmLayout());
+                       int K, int split_limit = kGemmMaxSplits, const GemmLayout &lay = GemmLayout(),
+                       const RowScale &scale = RowScale());
 // The same product with the greedy decode fused in: no C; per row and per column slice (a wave's
 // share of a tile, *parts of them) the maximum of the bf16-rounded values, the sum of
 // exp(x - max) and the lowest column holding the maximum, column mask_id left out.
 // stats: fp32/int32 planes [3][*parts][M]; *parts <= gemm_rowstats_max_parts(N).
 size_t gemm_rowstats_max_parts(int N);
 hipError_t launch_gemm_rowstats(hipStream_t stream, const void *A, const void *W, float *stats, int M, int N, int K,
-                                int mask_id, int *parts, const GemmLayout &lay = GemmLayout());
+                                int mask_id, int *parts, const GemmLayout &lay = GemmLayout(),
+                                const RowScale &scale = RowScale());
 
 }  // namespace dllm

@@ -304,6 +304,36 @@ def test_forward_without_panel_major_weight_copies(monkeypatch):
         logits_close(got, ref)
 
 
+def test_forward_with_the_separate_residual_add_and_rmsnorm_kernel(monkeypatch):
+    """DLLM_NO_FUSED_NORM: the O and down projections leave fp32 split-K slabs and a separate kernel adds
+    them to the residual stream and normalises (the default folds both into the projections)."""
+    monkeypatch.setenv("DLLM_NO_FUSED_NORM", "1")
+    for name, batch in (("tiny", 2), ("medium", 1)):
+        got, ref = run_forward(synth.CONFIGS[name], batch)
+        logits_close(got, ref)
+
+
+@pytest.mark.parametrize("epi,tile,splits", [(6, t, s) for t in (1, 2, 3, 4, 5, 6, 7, 8, 9) for s in (1, 2, 3)] +
+                         [(e, t, 0) for e in (1, 3, 5) for t in (0, 1, 2, 3, 4, 7, 8, 9)])
+def test_forward_tiny_config_every_tile_shape_of_the_fused_epilogues(epi, tile, splits, monkeypatch):
+    """The whole forward with one product family forced onto each tile shape (and K split count): 6 = O and
+    down projection with the residual add, the bf16(x * gain) operand and the row sums of squares in the
+    epilogue (more than one split: the tile's last-arriving workgroup adds the partial tiles up); 1, 3, 5 =
+    gate/up + SwiGLU, QKV + RoPE, vocabulary projection, each scaling its rows by the folded RMSNorm."""
+    monkeypatch.setenv(f"DLLM_GEMM_CFG_E{epi}", str(tile))
+    if splits:
+        monkeypatch.setenv("DLLM_GEMM_SPLITS", str(splits))
+        monkeypatch.setenv("DLLM_GEMM_CFG_E2", str(tile))     # (the planner asks the slab epilogue for the split count)
+        monkeypatch.setenv("DLLM_FUSED_SPLITK", "1")          # sum the K splits inside the projection too
+    cfg = dict(synth.CONFIGS["tiny"], d_ffn=704, prompt=100, gen=89)      # K = 704 = 11 * 64: three splits of 4, 4, 3 steps
+    got, ref = run_forward(cfg, 2)
+    logits_close(got, ref)
+    if epi == 6 and tile == 4:        # and the register-staged kernel with the same epilogue
+        monkeypatch.setenv("DLLM_GEMM_FALLBACK", "1")
+        got, ref = run_forward(cfg, 2)
+        logits_close(got, ref)
+
+
 def test_forward_tiny_config_wide_init_batch3():
     cfg = synth.CONFIGS["tiny"]
     got, ref = run_forward(cfg, 3, std=0.06)        # larger activations, stronger attention
