@@ -380,53 +380,60 @@ __device__ __forceinline__ void residual_tile(floatx16 (&acc)[TM][TN], const flo
                                               int n0, int wm, int wn, int l32, int lhalf, int part, const RopeArgs &ea)
 {
     const size_t slab = (size_t)M * N;
-    constexpr int NV = TN * 4;        // float4 positions of a lane in one 32-row block
+    constexpr int NV = TN * 4;              // float4 positions of a lane in one 32-row block
+    constexpr int NC = NV > 8 ? 8 : NV;     // handled at a time: the widest tiles have no registers for more
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int row = m0 + wm * WTM + i * 32 + l32;
-        float4 v[NV];
-        bool ok[NV];
-#pragma unroll
-        for (int jq = 0; jq < NV; ++jq) {
-            const int col = n0 + (wn * TN + jq / 4) * 32 + 8 * (jq % 4) + 4 * lhalf;
-            ok[jq] = row < M && col < N;                          // (N % 4 == 0: checked by the host)
-            v[jq] = ok[jq] ? *reinterpret_cast<const float4 *>(ea.x + (size_t)row * N + col) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        }
-        if constexpr (FROM_SLABS) {
-            for (int s = 0; s < splits; ++s) {
-                float4 p[NV];
-#pragma unroll
-                for (int jq = 0; jq < NV; ++jq) {
-                    const int col = n0 + (wn * TN + jq / 4) * 32 + 8 * (jq % 4) + 4 * lhalf;
-                    p[jq] = ok[jq] ? *reinterpret_cast<const float4 *>(slabs + s * slab + (size_t)row * N + col)
-                                   : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                }
-#pragma unroll
-                for (int jq = 0; jq < NV; ++jq) { v[jq].x += p[jq].x; v[jq].y += p[jq].y; v[jq].z += p[jq].z; v[jq].w += p[jq].w; }
-            }
-        } else {
-#pragma unroll
-            for (int jq = 0; jq < NV; ++jq) {
-                const int j = jq / 4, q = jq % 4;
-                v[jq].x += acc[i][j][4 * q]; v[jq].y += acc[i][j][4 * q + 1]; v[jq].z += acc[i][j][4 * q + 2]; v[jq].w += acc[i][j][4 * q + 3];
-            }
-        }
         float ss = 0.0f;
 #pragma unroll
-        for (int jq = 0; jq < NV; ++jq) {
-            if (!ok[jq]) continue;
-            const int col = n0 + (wn * TN + jq / 4) * 32 + 8 * (jq % 4) + 4 * lhalf;
-            const size_t at = (size_t)row * N + col;
-            const float4 t = v[jq];
-            *reinterpret_cast<float4 *>(ea.x + at) = t;
-            ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
-            const uint2 g = *reinterpret_cast<const uint2 *>(ea.gain + col);
-            uint2 o;
-            o.x = pack_bf16x2(t.x * bf16_lo(g.x), t.y * bf16_hi(g.x));
-            o.y = pack_bf16x2(t.z * bf16_lo(g.y), t.w * bf16_hi(g.y));
-            uint16_t *hp = ea.c_panel_rows ? ea.h_out + ((size_t)(col >> 5) * ea.c_panel_rows + row) * 32 + (col & 31)
-                                           : ea.h_out + at;
-            *reinterpret_cast<uint2 *>(hp) = o;
+        for (int c0 = 0; c0 < NV; c0 += NC) {
+            float4 v[NC];
+            bool ok[NC];
+#pragma unroll
+            for (int u = 0; u < NC; ++u) {
+                const int jq = c0 + u;
+                const int col = n0 + (wn * TN + jq / 4) * 32 + 8 * (jq % 4) + 4 * lhalf;
+                ok[u] = row < M && col < N;                       // (N % 4 == 0: checked by the host)
+                v[u] = ok[u] ? *reinterpret_cast<const float4 *>(ea.x + (size_t)row * N + col) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            }
+            if constexpr (FROM_SLABS) {
+                for (int s = 0; s < splits; ++s) {
+                    float4 p[NC];
+#pragma unroll
+                    for (int u = 0; u < NC; ++u) {
+                        const int jq = c0 + u;
+                        const int col = n0 + (wn * TN + jq / 4) * 32 + 8 * (jq % 4) + 4 * lhalf;
+                        p[u] = ok[u] ? *reinterpret_cast<const float4 *>(slabs + s * slab + (size_t)row * N + col)
+                                     : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    }
+#pragma unroll
+                    for (int u = 0; u < NC; ++u) { v[u].x += p[u].x; v[u].y += p[u].y; v[u].z += p[u].z; v[u].w += p[u].w; }
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < NC; ++u) {
+                    const int j = (c0 + u) / 4, q = (c0 + u) % 4;
+                    v[u].x += acc[i][j][4 * q]; v[u].y += acc[i][j][4 * q + 1]; v[u].z += acc[i][j][4 * q + 2]; v[u].w += acc[i][j][4 * q + 3];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < NC; ++u) {
+                if (!ok[u]) continue;
+                const int jq = c0 + u;
+                const int col = n0 + (wn * TN + jq / 4) * 32 + 8 * (jq % 4) + 4 * lhalf;
+                const size_t at = (size_t)row * N + col;
+                const float4 t = v[u];
+                *reinterpret_cast<float4 *>(ea.x + at) = t;
+                ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+                const uint2 g = *reinterpret_cast<const uint2 *>(ea.gain + col);
+                uint2 o;
+                o.x = pack_bf16x2(t.x * bf16_lo(g.x), t.y * bf16_hi(g.x));
+                o.y = pack_bf16x2(t.z * bf16_lo(g.y), t.w * bf16_hi(g.y));
+                uint16_t *hp = ea.c_panel_rows ? ea.h_out + ((size_t)(col >> 5) * ea.c_panel_rows + row) * 32 + (col & 31)
+                                               : ea.h_out + at;
+                *reinterpret_cast<uint2 *>(hp) = o;
+            }
         }
         ss += __shfl_xor(ss, 32, 64);                               // the other half of the row's columns
         if (lhalf == 0 && row < M) ea.ssq_out[(size_t)row * ea.ssq_out_stride + part] = ss;
@@ -823,11 +830,12 @@ struct Plan {
 
 // Test and tuning hooks from the environment, read once (and again by gemm_reload_env): DLLM_GEMM_FALLBACK
 // forces the register-staged kernel, DLLM_NO_FUSED_ROPE the separate rotary kernel, DLLM_GEMM_CFG a tile
-// shape for every product, DLLM_GEMM_CFG_E<epilogue> for one epilogue, DLLM_GEMM_SPLITS a split count.
+// shape for every product, DLLM_GEMM_CFG_E<epilogue> for one epilogue, DLLM_GEMM_SPLITS a split count;
+// DLLM_GEMM_ONLY_K restricts the tile and split overrides to products with that inner dimension.
 constexpr int kNumEpi = 7;
 struct EnvHooks {
     bool loaded = false;
-    int fallback = 0, no_fused_rope = 0, cfg_all = -1, cfg_epi[kNumEpi] = {-1, -1, -1, -1, -1, -1, -1}, splits = -1;
+    int fallback = 0, no_fused_rope = 0, cfg_all = -1, cfg_epi[kNumEpi] = {-1, -1, -1, -1, -1, -1, -1}, splits = -1, only_k = 0;
 };
 std::mutex g_plan_mutex;  // guards g_env and g_plans
 EnvHooks g_env;
@@ -850,6 +858,7 @@ void load_env_locked()
         g_env.cfg_epi[e] = env_int(name, -1);
     }
     g_env.splits = env_int("DLLM_GEMM_SPLITS", -1);
+    g_env.only_k = env_int("DLLM_GEMM_ONLY_K", 0);
     g_env.loaded = true;
 }
 
@@ -864,8 +873,9 @@ EnvHooks env_hooks()
 bool cfg_allows(int c, int epi, bool fast)
 {
     if (!fast && c < 2) return false;  // the register-staged kernel keeps to the smaller tiles
-    // 256 accumulator registers per lane leave no room for the addresses of the fp32 epilogue (and at
-    // N = 4096 it measured no faster than the 256x128 tile)
+    // 256 accumulator registers per lane leave no room for the addresses of the fp32 epilogues (the residual
+    // epilogue compiles with 360 bytes of scratch per lane), and at N = 4096 it measured no faster than the
+    // 256x128 tile (B = 8, L = 1536: 162.4-162.6 ms per step either way)
     if (c == 0 && (epi == kEpiPartial || epi == kEpiResidual)) return false;
     // a wave's slice of a row is at least 64 columns wide, which bounds the partial results per row
     if (epi == kEpiRowStats && kCfg[c].bn / kCfg[c].wn < 64) return false;
@@ -879,7 +889,9 @@ Plan search_plan(const EnvHooks &env, int epi, int M, int N, int K, int split_li
     const int n_out = epi == kEpiSwiglu ? N / 2 : N;
     // the asynchronous-copy kernel needs whole K-steps and 32-bit byte offsets
     const bool fast = (K % 64 == 0) && ((double)M * K * 2 < 4.0e9) && ((double)N * K * 2 < 4.0e9) && env.fallback == 0;
-    const int fc = (epi >= 0 && epi < kNumEpi && env.cfg_epi[epi] >= 0) ? env.cfg_epi[epi] : env.cfg_all, fs = env.splits;
+    const bool forced = env.only_k <= 0 || env.only_k == K;
+    const int fc = !forced ? -1 : (epi >= 0 && epi < kNumEpi && env.cfg_epi[epi] >= 0) ? env.cfg_epi[epi] : env.cfg_all;
+    const int fs = forced ? env.splits : -1;
     Plan best{4, 1, fast};
     double best_cost = 1e300;
     const bool splittable = epi == kEpiPartial || epi == kEpiResidual;
