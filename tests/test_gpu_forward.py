@@ -223,6 +223,8 @@ def test_linear_qkv_rope(B, L, H, dh, theta, tile, monkeypatch):
 
 @pytest.mark.parametrize("B,L,H,dh", [(1, 96, 4, 64), (2, 200, 2, 128), (1, 64, 1, 64), (1, 129, 2, 128),
                                       (5, 384, 16, 64), (1, 17, 2, 128), (2, 600, 3, 128),
+                                      # odd numbers of key steps per half, a ragged last step, 16 steps
+                                      (1, 257, 2, 64), (1, 320, 4, 128), (1, 1024, 8, 64), (3, 1000, 2, 128),
                                       # >= 1024 workgroups: the variant without the in-workgroup key split
                                       (8, 200, 64, 64), (9, 130, 64, 128)])
 def test_attention(B, L, H, dh):
