@@ -294,14 +294,18 @@ int run_layers(dllm_handle *h, const int32_t *tokens, const LayerRun &r, int *h_
         const void *wqkv = pd ? h->wqkv_p[l] : h->wqkv[l];
         const GemmLayout lq{pd, pd ? 3 * d : 0, 0};
         void *qkv_out = r.to_cache ? (void *)w.kv_cache[l] : (void *)w.qkv;
+        // a forward over gathered rows: the rotary epilogue puts keys and values at their rows of the cache
+        const bool scatter_in_epilogue = fused_rope && r.kv_rows && !r.to_cache;
         if (fused_rope) {
-            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, wqkv, qkv_out, M, d, c.head_dim, w.rope, r.L, r.pos_d, lq, sc));
+            HIP_TRY(h, launch_gemm_qkv_rope(st, w.h, wqkv, qkv_out, M, d, c.head_dim, w.rope, r.L, r.pos_d, lq, sc,
+                                            scatter_in_epilogue ? (void *)w.kv_cache[l] : nullptr,
+                                            scatter_in_epilogue ? r.rows_d : nullptr));
         } else {
             HIP_TRY(h, launch_gemm(st, kEpiBf16, w.h, wqkv, qkv_out, M, 3 * d, d, kGemmMaxSplits, lq, sc));
             HIP_TRY(h, launch_rope(st, qkv_out, w.rope, r.B, r.L, c.n_heads, c.head_dim, c.rope_theta));
         }
         if (r.kv_rows) {
-            if (!r.to_cache) HIP_TRY(h, launch_scatter_kv(st, w.qkv, w.kv_cache[l], r.rows_d, M, d));
+            if (!r.to_cache && !scatter_in_epilogue) HIP_TRY(h, launch_scatter_kv(st, w.qkv, w.kv_cache[l], r.rows_d, M, d));
             HIP_TRY(h, launch_attention_rows(st, qkv_out, w.kv_cache[l], w.att, r.B, r.L, c.n_heads, c.head_dim, *r.kv_rows, pd));
         } else {
             HIP_TRY(h, launch_attention(st, w.qkv, w.att, r.B, r.L, c.n_heads, c.head_dim, pd));

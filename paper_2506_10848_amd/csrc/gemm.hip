@@ -149,11 +149,13 @@ struct RopeArgs {
     int ssq_parts, ssq_stride;
     float eps;
     // Residual epilogue (see ResidualOut); Cout then holds the fp32 split-K slabs.
+    // (the rotary epilogues use two of its fields for their own purpose: with kv_dst set, the K and V thirds of
+    // output row r go to row kv_rows[r] of kv_dst, a [rows][3 d] array, instead of row r of Cout)
     float *x;
     const uint16_t *gain;
-    uint16_t *h_out;
+    union { uint16_t *h_out; uint16_t *kv_dst; };
     float *ssq_out;
-    int *tickets;
+    union { int *tickets; const int32_t *kv_rows; };
     int ssq_out_stride;
 };
 constexpr int kEpiRope64 = 3, kEpiRope128 = 4;  // head_dim is a compile-time constant of the epilogue
@@ -287,6 +289,10 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
             const int row = m0 + wm * WTM + i * 32 + l32;
             const float2 *trow = rope.table + (size_t)(rope.pos ? rope.pos[min(row, M - 1)] : row % rope.L) * HD;
             const float inv = s_inv ? s_inv[wm * WTM + i * 32 + l32] : 1.0f;
+            // keys and values of a gathered row go straight to the row's place in the cache
+            uint16_t *crow = C + (size_t)row * N;
+            uint16_t *kvrow = rope.kv_dst ? rope.kv_dst + (size_t)rope.kv_rows[min(row, M - 1)] * N : crow;
+            const int kv_first = N / 3;
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -311,13 +317,14 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], void *Cout, 
                             b[e] = x * sn[e] + y * cs[e];
                         }
                     }
+                    uint16_t *dst = (col >= kv_first ? kvrow : crow) + col;   // (a pair never straddles two thirds)
                     uint2 w;
                     w.x = pack_bf16x2(a[0], a[1]);
                     w.y = pack_bf16x2(a[2], a[3]);
-                    *reinterpret_cast<uint2 *>(C + (size_t)row * N + col) = w;
+                    *reinterpret_cast<uint2 *>(dst) = w;
                     w.x = pack_bf16x2(b[0], b[1]);
                     w.y = pack_bf16x2(b[2], b[3]);
-                    *reinterpret_cast<uint2 *>(C + (size_t)row * N + col + HD) = w;
+                    *reinterpret_cast<uint2 *>(dst + HD) = w;
                 }
         }
     } else if (EPI == kEpiBf16) {
@@ -1043,10 +1050,13 @@ bool gemm_qkv_rope_supported(int M, int d, int dh)
 }
 
 hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
-                                const float2 *table, int L, const int32_t *pos, const GemmLayout &lay, const RowScale &scale)
+                                const float2 *table, int L, const int32_t *pos, const GemmLayout &lay, const RowScale &scale,
+                                void *kv_dst, const int32_t *kv_rows)
 {
+    if ((kv_dst == nullptr) != (kv_rows == nullptr)) return hipErrorInvalidValue;
     RopeArgs rope{};
     rope.table = table; rope.pos = pos; rope.L = L; rope.rope_cols = 2 * d;
+    rope.kv_dst = reinterpret_cast<uint16_t *>(kv_dst); rope.kv_rows = kv_rows;
     set_scale(rope, scale);
     const Plan p = make_plan(dh == 128 ? kEpiRope128 : kEpiRope64, M, 3 * d, d);
     if (dh == 128) return dispatch<kEpiRope128>(stream, p, A, W, C, M, 3 * d, d, lay, rope);

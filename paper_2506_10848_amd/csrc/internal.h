@@ -131,10 +131,13 @@ void gemm_reload_env();
 // QKV projection with the rotary embedding of the q and k thirds fused into the
 // epilogue: C bf16 [M][3d] = A[M][d] * W[3d][d]^T, rows are positions row % L.
 bool gemm_qkv_rope_supported(int M, int d, int dh);
-// pos (nullable): position of every row; default row % L.
+// pos (nullable): position of every row; default row % L.  kv_dst / kv_rows (both or neither): the K and V
+// thirds of output row r are written to row kv_rows[r] of kv_dst ([rows][3 d], e.g. a key/value cache) and
+// only the Q third to row r of C.
 hipError_t launch_gemm_qkv_rope(hipStream_t stream, const void *A, const void *W, void *C, int M, int d, int dh,
                                 const float2 *table, int L, const int32_t *pos = nullptr,
-                                const GemmLayout &lay = GemmLayout(), const RowScale &scale = RowScale());
+                                const GemmLayout &lay = GemmLayout(), const RowScale &scale = RowScale(),
+                                void *kv_dst = nullptr, const int32_t *kv_rows = nullptr);
 // C = A[M][K] * W[N][K]^T.  For kEpiSwiglu N counts gate + up rows.
 hipError_t launch_gemm(hipStream_t stream, GemmEpilogue epi, const void *A, const void *W, void *C, int M, int N,
                        int K, int split_limit = kGemmMaxSplits, const GemmLayout &lay = GemmLayout(),
