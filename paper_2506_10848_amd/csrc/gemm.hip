@@ -388,7 +388,9 @@ __device__ __forceinline__ void residual_tile(floatx16 (&acc)[TM][TN], const flo
 {
     const size_t slab = (size_t)M * N;
     constexpr int NV = TN * 4;              // float4 positions of a lane in one 32-row block
-    constexpr int NC = NV > 8 ? 8 : NV;     // handled at a time: the widest tiles have no registers for more
+    // handled at a time (a divisor of NV): the widest tiles have no registers for more
+    constexpr int NC = NV <= 8 ? NV : NV % 8 == 0 ? 8 : NV % 6 == 0 ? 6 : 4;
+    static_assert(NV % NC == 0, "whole chunks");
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int row = m0 + wm * WTM + i * 32 + l32;
