@@ -39,6 +39,27 @@ def gemm_kernel_name(b, epi, M, N, K, what):
             f"{p['splits']} K split(s), {what}>")
 
 
+def sustained_mfma(b, torch):
+    """dllm_debug_mfma_rate: 256 workgroups x 4 waves x 40000 x 8 MFMAs (about 6 ms), best of 3, per operand kind."""
+    g = torch.Generator(device="cuda"); g.manual_seed(7)
+    sink = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+    out = {"kernel": "v_mfma_f32_32x32x16_bf16 on register operands, 8 independent accumulator tiles per wave, "
+                     "256 workgroups of 4 waves, 40000 iterations"}
+    for name, ops in (("random_operands_TFLOPs", torch.randn(1 << 19, device="cuda", generator=g).to(torch.bfloat16)),
+                      ("zero_operands_TFLOPs", torch.zeros(1 << 19, dtype=torch.bfloat16, device="cuda"))):
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flop = b.debug_mfma_rate(ops, sink, 256, 40000)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None or ms < best else best
+        out[name] = flop / (best * 1e-3) / 1e12
+    return out
+
+
 def long_batch_extra(b, synth, torch, weights, mc):
     """B = 8, L = 512 + 1024 on the same LLaDA-8B-shaped weights: one timed step (slow stage over the whole
     generated region) and a SlowFast decode capped at a stated number of steps with thresholds at quantiles
@@ -323,6 +344,11 @@ def main():
             ("down", 2, B * L, mc["d_model"], mc["d_ffn"]),
             ("vocab_rowstats", 5, B * G, mc["vocab"], mc["d_model"])]},
     }
+
+    # What the matrix cores sustain when nothing else runs (registers only, one wave per SIMD on every CU): with
+    # random operands the power limit sets it well below the nominal peak; all-zero operands reach the peak.
+    result["roofline"]["sustained_mfma"] = sustained_mfma(b, torch)
+    result["roofline"]["frac_of_sustained_random"] = achieved / result["roofline"]["sustained_mfma"]["random_operands_TFLOPs"]
 
     if args.pmc_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")          # 1 GiB read + 1 GiB written

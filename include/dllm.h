@@ -276,6 +276,16 @@ void dllm_debug_reload_env(void);
  * grid rows, wave grid columns, K splits, 1 for the asynchronous-copy kernel / 0 for the register-staged one. */
 int dllm_debug_gemm_plan(int32_t epilogue, int32_t M, int32_t N, int32_t K, int32_t split_limit, int32_t *out8);
 int dllm_debug_rows(dllm_handle *h, const int32_t **pred, const float **conf);
+/* Measurement hook: the sustained rate of the bf16 matrix instruction itself (the practical ceiling of the
+ * projections: with random operands the chip's power limit sets it well below the nominal peak).  Enqueues one
+ * kernel on hip_stream in which each of `workgroups` workgroups of four waves executes iters * 8 instructions
+ * v_mfma_f32_32x32x16_bf16 on operands held in registers (32768 flop each, so a launch performs
+ * workgroups * 4 * iters * 8 * 32768 flop); the caller times it.  operands (device): n_operands >= 1 pieces of
+ * 16 bytes holding the bf16 values to multiply, read once per wave; sink (device): workgroups * 256 floats that
+ * receive the accumulator sums.  workgroups and iters in [1, 2^20].  Returns DLLM_EINVAL for a null pointer or a
+ * count out of range, DLLM_EHIP if the launch fails. */
+int dllm_debug_mfma_rate(void *hip_stream, const void *operands, int32_t n_operands, float *sink,
+                         int32_t workgroups, int32_t iters);
 
 /* Measurement hook for the kernel that carries the most flops of a step, the
  * gate/up projection GEMM with the SwiGLU epilogue (one launch per layer):

@@ -62,7 +62,7 @@ class StepStat(C.Structure):
                 ("ms", C.c_float)]
 
 
-EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_step_cached", "dllm_decode", "dllm_decode_low_confidence", "dllm_set_fused_selector", "dllm_sync_status", "dllm_debug_reload_env", "dllm_debug_gemm_plan", "dllm_debug_logits",
+EXPORTS = ["dllm_create", "dllm_destroy", "dllm_last_error", "dllm_step", "dllm_step_cached", "dllm_decode", "dllm_decode_low_confidence", "dllm_set_fused_selector", "dllm_sync_status", "dllm_debug_reload_env", "dllm_debug_gemm_plan", "dllm_debug_mfma_rate", "dllm_debug_logits",
            "dllm_debug_rows", "dllm_profile_begin", "dllm_profile_end", "dllm_forward", "dllm_select", "dllm_op_linear", "dllm_op_linear_swiglu", "dllm_op_pack_panels", "dllm_op_linear_panels",
            "dllm_op_add_rmsnorm", "dllm_op_rope", "dllm_op_linear_qkv_rope", "dllm_op_linear_qkv_rope_static", "dllm_op_attention"]
 
@@ -85,6 +85,14 @@ def lib() -> C.CDLL:
         _lib.dllm_debug_reload_env.restype = None
         _lib.dllm_debug_reload_env.argtypes = []
     return _lib
+
+
+def debug_mfma_rate(operands, sink, workgroups: int, iters: int) -> float:
+    """dllm_debug_mfma_rate on the current stream; returns the flop count of the launch (the caller times it)."""
+    _dev(operands, torch.bfloat16, "operands"); _dev(sink, torch.float32, "sink")
+    assert operands.numel() % 8 == 0 and sink.numel() >= workgroups * 256
+    _check(lib().dllm_debug_mfma_rate(_stream(), _ptr(operands), operands.numel() // 8, _ptr(sink), workgroups, iters))
+    return workgroups * 4.0 * iters * 8 * 32768
 
 
 def gemm_plan(epilogue: int, M: int, N: int, K: int, split_limit: int = 8) -> dict:

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdllm.so")
-SOURCES = ["dllm_api.hip", "selector.hip", "elementwise.hip", "gemm.hip", "attention.hip"]
+SOURCES = ["dllm_api.hip", "selector.hip", "elementwise.hip", "gemm.hip", "attention.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed fp32 instructions stay off on the test machines

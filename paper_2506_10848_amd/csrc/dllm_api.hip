@@ -1061,6 +1061,16 @@ int dllm_debug_gemm_plan(int32_t epilogue, int32_t M, int32_t N, int32_t K, int3
     return DLLM_OK;
 }
 
+int dllm_debug_mfma_rate(void *hip_stream, const void *operands, int32_t n_operands, float *sink, int32_t workgroups,
+                         int32_t iters)
+{
+    if (!operands || !sink) return fail(nullptr, DLLM_EINVAL, "dllm_debug_mfma_rate: null pointer");
+    if (n_operands < 1 || workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 20))
+        return fail(nullptr, DLLM_EINVAL, "dllm_debug_mfma_rate: n_operands >= 1, workgroups and iters in [1, 2^20]");
+    HIP_TRY(nullptr, launch_mfma_rate(static_cast<hipStream_t>(hip_stream), operands, n_operands, sink, workgroups, iters));
+    return DLLM_OK;
+}
+
 int dllm_debug_logits(dllm_handle *h, const void **logits)
 {
     if (!h || !logits) return fail(h, DLLM_EINVAL, "dllm_debug_logits: null argument");

@@ -63,6 +63,10 @@ struct SeqRows {
 hipError_t launch_attention_rows(hipStream_t stream, const void *q, const void *kv, void *out, int B, int Lk, int H,
                                  int dh, const SeqRows &rows, int out_panel_rows = 0);
 
+// sink[workgroups * 256] floats; operands: n_operands pieces of 16 bytes (bf16 values); see probe.hip
+hipError_t launch_mfma_rate(hipStream_t stream, const void *operands, int n_operands, float *sink, int workgroups,
+                            int iters);
+
 enum GemmEpilogue {
     kEpiBf16 = 0,     // C bf16 [M][N]
     kEpiSwiglu = 1,   // W = [gate | up] rows; C bf16 [M][N/2] = silu(gate) * up

@@ -547,3 +547,25 @@ def test_step_cached_argument_checks():
         model.step_cached(tokens, mask, prev, slow, [b.CACHE_REUSE], skip, out)
     torch.cuda.synchronize()
     model.close()
+
+
+def test_mfma_rate_hook_runs_and_rejects_bad_counts():
+    """dllm_debug_mfma_rate: the sums it leaves are finite and nonzero for nonzero operands, zero for zero
+    operands; counts out of range are refused before anything is launched."""
+    import ctypes as C
+    b = binding()
+    ops = synth.normal_bf16((4096,), 1.0, 5, "mfma", DEV)
+    sink = torch.full((4 * 256,), float("nan"), dtype=torch.float32, device=DEV)
+    flop = b.debug_mfma_rate(ops, sink, 4, 10)
+    torch.cuda.synchronize()
+    assert flop == 4 * 4 * 10 * 8 * 32768
+    got = sink.cpu().numpy()
+    assert np.isfinite(got).all() and (got != 0).any()
+    b.debug_mfma_rate(torch.zeros_like(ops), sink, 4, 10)
+    torch.cuda.synchronize()
+    assert (sink.cpu().numpy() == 0).all()
+    lib = b.lib()
+    st = torch.cuda.current_stream().cuda_stream
+    for wgs, iters in ((0, 10), (4, 0), (1 << 21, 1)):
+        assert lib.dllm_debug_mfma_rate(C.c_void_p(st), C.c_void_p(ops.data_ptr()), 512, C.c_void_p(sink.data_ptr()), wgs, iters) < 0
+    assert lib.dllm_debug_mfma_rate(C.c_void_p(st), None, 512, C.c_void_p(sink.data_ptr()), 4, 10) < 0
