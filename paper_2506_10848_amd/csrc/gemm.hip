@@ -918,9 +918,10 @@ Plan search_plan(const EnvHooks &env, int epi, int M, int N, int K, int split_li
     const int max_splits = splittable ? (split_limit < 1 ? 1 : split_limit > kGemmMaxSplits ? kGemmMaxSplits : split_limit) : 1;
     for (int c = 0; c < kNumCfg; ++c) {
         if (!cfg_allows(c, epi, fast) || (fc >= 0 && fc < kNumCfg && cfg_allows(fc, epi, fast) && c != fc)) continue;
-        // a single row of 256x256 tiles that only streams W (the vocabulary projection of one window) measures
-        // 315 us where the model says 271 and the 256x128 tile takes 284: the largest tile waits for four row tiles
-        if (c == 0 && fc != 0 && M < 1024 && (epi == kEpiRowStats || epi == kEpiBf16) && N > 16 * K) continue;
+        // a single row of 256x256 tiles that only streams W and writes bf16 logits measured 315 us where the model
+        // says 271 and the 256x128 tile takes 284 (row-major operands); with the row-statistics epilogue, panel-major
+        // weights and non-temporal copies the largest tile is the fastest (228 vs 250-257 us at 256 rows) and stays in
+        if (c == 0 && fc != 0 && M < 1024 && epi == kEpiBf16 && N > 16 * K) continue;
         const TileCfg &t = kCfg[c];
         const int bn_out = epi == kEpiSwiglu ? t.bn / 2 : t.bn;
         const long tiles = (long)((M + t.bm - 1) / t.bm) * ((n_out + bn_out - 1) / bn_out);
